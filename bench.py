@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Benchmark of the AdaSD verification hot path on one MI355X.
+
+One step = one decode round's verification on the headline workload (B=32 sequences, k=8 drafted
+positions, V=128256, bf16 logits resident in HBM): adasd_verify (normalisers, entropies, JS distance,
+posterior, both acceptance tests, first reject, correction/bonus token) followed by
+adasd_update_thresholds.  Inputs rotate over several distinct seeded batches (> 512 MB in total) so
+that no cache carries logits from one step to the next.
+
+Prints ONE JSON line: throughput in verified positions/s, the HBM roofline fraction of the
+statistics kernels (algorithmic bytes / measured kernel time), and the CPU oracle timed on the same
+workload as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+B, K, V = 32, 8, 128256
+N_SETS = 4                     # 4 x 139.5 MB of logits
+LIST_CAP = 8192
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sets", type=int, default=N_SETS)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (sequences are independent, so the "
+                 "path shards by sequence with no communication); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import paper_2512_11280_amd as am
+    from paper_2512_11280_amd import workloads as wl
+
+    am.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    # ---- seeded synthetic inputs, resident in HBM before any timing
+    sets = []
+    host0 = None
+    for i in range(args.sets):
+        batch = wl.config_batched(seed=wl.DEFAULT_SEED + 2 + 100 * i, B=B, k=K, V=V, cap=LIST_CAP)
+        if i == 0:
+            host0 = batch
+        sets.append((batch.target.cuda(), batch.draft.cuda(), batch.draft_tokens.cuda(), batch.seed))
+    ws = am.Workspace(B, K, V, torch.bfloat16)
+    state = am.State(B, LIST_CAP).load(host0.state)
+    out = am.binding.alloc_verify_result(B, K)
+    torch.cuda.synchronize()
+
+    def step(i):
+        t, d, x, seed = sets[i % len(sets)]
+        am.verify(t, d, x, ws, state=state, seed=seed, round0=i, out=out)
+        am.update_thresholds(state, K, out.n_accept, out.H_q, out.d_js)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` steps
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    positions_per_s = B * K * args.steps / elapsed
+
+    # ---- the same steps again with HIP events around each kernel class (library-side, on the
+    #      launch stream): per-kernel durations for the roofline figure
+    am.profile_enable(args.steps)
+    state.load(host0.state)
+    torch.cuda.synchronize()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    names = ["row_stats", "jsd", "decide", "sample", "update", "draft_entropy"]
+    kern_us = {}
+    for c, name in enumerate(names):
+        ms, n = am.profile_read(c)
+        if n:
+            kern_us[name] = ms / n * 1e3
+    am.profile_disable()
+    mean_accept = float(out.n_accept.float().mean().item())
+
+    # Algorithmic bytes of one launch of the statistics stage: every target and draft logit of the
+    # B*k verified positions once.  While the stage is two kernels (normalisers, then JS distance)
+    # the second read of the same bytes is not counted, so the fraction is against ONE read.
+    algo_bytes = 2 * V * 2 * B * K
+    stats_us = kern_us.get("row_stats", 0.0) + kern_us.get("jsd", 0.0)
+    achieved = algo_bytes / (stats_us * 1e-6) / 1e9 if stats_us > 0 else 0.0
+
+    # ---- draft-side call (one [B, V] row block per drafted token), reported on the side
+    rows = sets[0][1][:, 0]
+    H = torch.empty(B, dtype=torch.float32, device="cuda")
+    stop = torch.empty(B, dtype=torch.uint8, device="cuda")
+    for _ in range(10):
+        am.draft_entropy(rows, ws, T_G=state.T_G, step=0, k_max=20, H_out=H, stop_out=stop)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for i in range(200):
+        am.draft_entropy(sets[i % len(sets)][1][:, i % K], ws, T_G=state.T_G, step=0, k_max=20,
+                         H_out=H, stop_out=stop)
+    torch.cuda.synchronize()
+    draft_us = (time.perf_counter() - t1) / 200 * 1e6
+
+    # ---- CPU oracle on the same workload (baseline, not a target)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import load_oracle
+        ora = load_oracle()
+        s = host0.state
+        reps = 3
+        c0 = time.perf_counter()
+        for r in range(reps):
+            ora.verify(host0.target, host0.draft, host0.draft_tokens.numpy(), LA=s["LA"], LR=s["LR"],
+                       nA=s["nA"], nR=s["nR"], seed=host0.seed, round0=r)
+        c1 = time.perf_counter()
+        cpu = {"value": B * K * reps / (c1 - c0), "unit": "verified positions/s",
+               "cores": ora.num_threads(), "kind": "oracle",
+               "sample": f"full workload batch 0 (B={B}, k={K}, V={V}: {B * K} positions + {B} sampled "
+                         f"tokens), {reps} repetitions, float64 C oracle with OpenMP over sequences"}
+
+    line = {
+        "metric": "verified positions/sec and achieved HBM GB/s (% peak) at B=32,k=8,V=128256 bf16",
+        "value": positions_per_s,
+        "unit": "verified positions/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"batched verify B={B} k={K} V={V} bf16 logits, "
+                               f"{len(sets)} rotating seeded input sets, history lists 64+64 per sequence",
+                   "step": "adasd_verify + adasd_update_thresholds"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "row_stats + jsd (statistics stage)", "algorithmic_bytes": algo_bytes,
+                     "kernel_us": stats_us},
+        "cpu_baseline": cpu,
+        "kernel_us": kern_us,
+        "draft_entropy_us_per_call": draft_us,
+        "mean_accepted_length": mean_accept,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

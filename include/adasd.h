@@ -1,0 +1,216 @@
+/*
+ * adasd.h -- C ABI of the MI355X (gfx950) library for the per-round statistics,
+ * verification and threshold update of Adaptive Speculative Decoding (AdaSD).
+ *
+ * One decode round of Algorithm 1 of the paper, seen from this library:
+ *   generation  : after every drafted token call adasd_draft_entropy on the draft
+ *                 logits; it returns H(q_i) and the stop flag H(q_i) > T_G
+ *                 (Section 4.3; generation loop of Algorithm 1);
+ *   verification: once the window is drafted call adasd_verify with the target and
+ *                 draft logits of the k candidates (Sections 2.1.3, 2.2, 4.4;
+ *                 verification loop of Algorithm 1);
+ *   update      : then adasd_update_thresholds folds the round's outcome into the
+ *                 history lists and the generation threshold (Section 4.3; update
+ *                 lines of Algorithm 1).
+ * The draft and target transformers are outside this library: it only sees logits.
+ *
+ * Conventions for every entry point
+ *   - returns 0 (ADASD_OK) or a negative ADASD_ERR_* code; never throws;
+ *   - every pointer is DEVICE memory owned by the caller unless the comment says
+ *     "host"; struct arguments themselves (adasd_state, adasd_verify_args,
+ *     adasd_options) are host structs holding device pointers;
+ *   - work is enqueued on the HIP stream passed as `stream` (a hipStream_t cast to
+ *     void*, NULL = the default stream); no entry point synchronises, allocates or
+ *     frees device memory;
+ *   - argument errors are detected on the host before anything is enqueued; problems
+ *     that depend on device data (token id outside the vocabulary, NaN/+inf logits,
+ *     full history list, ...) are reported per sequence in a `status` bit mask;
+ *   - logits are row-major with the vocabulary contiguous; strides are in ELEMENTS;
+ *     rows whose byte address is 16-byte aligned take the 128-bit load path, other
+ *     rows are still handled correctly by an element-wise path;
+ *   - units: entropies in nats; the Jensen-Shannon distance is reported as
+ *     d = sqrt(D_JS / ln 2), i.e. the base-2 normalisation under which the paper
+ *     states the [0,1] bound and the "exactly 0 or 1" exclusion (Sections 2.2, 4.4).
+ */
+#ifndef ADASD_H
+#define ADASD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { ADASD_F32 = 0, ADASD_BF16 = 1 } adasd_dtype;
+
+enum {
+  ADASD_OK = 0,
+  ADASD_ERR_INVALID_ARG = -1, /* NULL pointer, negative size, bad enum, bad stride */
+  ADASD_ERR_MISALIGNED = -2,  /* pointer below the natural alignment of its element type */
+  ADASD_ERR_UNSUPPORTED = -3, /* option value that is declared but not built */
+  ADASD_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than adasd_workspace_bytes */
+  ADASD_ERR_CAPACITY = -5,    /* size beyond a compiled limit (k_max, V, B) */
+  ADASD_ERR_HIP = -6          /* a HIP runtime call failed (launch error) */
+};
+
+/* Per-sequence status bits written by adasd_verify / adasd_update_thresholds. */
+enum {
+  ADASD_ST_BAD_TOKEN = 1u,   /* a draft token id was outside [0,V): that position fails the base test */
+  ADASD_ST_NONFINITE = 2u,   /* a needed row held NaN/+inf or no finite logit: its statistics are NaN,
+                                the position is rejected, a token drawn from such a row is -1 */
+  ADASD_ST_ZERO_MASS = 4u,   /* max(0, p - q) had no mass at the rejected position: token drawn from p */
+  ADASD_ST_OVERFLOW = 8u,    /* a history list was full: the append was dropped */
+  ADASD_ST_EXACT_PATH = 16u, /* informational: the float64 tie-resolution path chose the token */
+  ADASD_ST_BAD_LENGTH = 32u  /* draft_len[b] outside [0,k_max]: clamped */
+};
+
+/* Compiled limits. */
+#define ADASD_MAX_K 64            /* k_max <= 64 (the paper caps the window at W = 20) */
+#define ADASD_MAX_V (1 << 24)     /* vocabulary size */
+
+/*
+ * Per-sequence adaptive state of Algorithm 1 (initialisation block), structure of
+ * arrays.  L_E^R is only ever used through its mean, so it is kept as (sum, count).
+ */
+typedef struct {
+  int32_t B;        /* sequences */
+  int32_t cap;      /* capacity of each history list, per sequence */
+  float *T_G;       /* [B]      generation threshold, nats; initial value 0 */
+  double *ent_sum;  /* [B]      sum of H(q) over rejected candidates (L_E^R summed) */
+  int32_t *ent_cnt; /* [B]      |L_E^R| */
+  float *LA;        /* [B,cap]  JS distances of accepted candidates, values in (0,1) (L_D^A) */
+  float *LR;        /* [B,cap]  JS distances of rejected candidates, values in (0,1) (L_D^R) */
+  int32_t *nA;      /* [B]      |L_D^A| */
+  int32_t *nR;      /* [B]      |L_D^R| */
+} adasd_state;
+
+/*
+ * Readings of the points the paper leaves open; zero-initialised = the defaults.
+ */
+typedef struct {
+  int32_t base_test;   /* 0: speculative-sampling ratio test min(1,p/q) with re-sampling from
+                          max(0,p-q) (Section 2.1.3).  Other values: ADASD_ERR_UNSUPPORTED. */
+  int32_t reject_rule; /* the undefined Reject(P(A|d)) of Algorithm 1:
+                          0: Bernoulli, candidate kept if u < P(A|d);  1: MAP, kept if P(A|d) >= 1/2 */
+  int32_t kde_min_n;   /* the Bayesian test is off until both lists hold this many samples
+                          (values < 2 mean 2) and have non-zero variance */
+  int32_t bw_rule;     /* KDE bandwidth: 0 Silverman's reference rule (4/(3n))^(1/5) sigma,
+                          1 Scott's n^(-1/5) sigma; Gaussian kernel either way */
+  int32_t relaxed_off; /* 1: Bayesian test disabled (the "Gen-Only" ablation of Section 5.3) */
+  float d_eps;         /* distances <= d_eps or >= 1-d_eps count as "exactly 0 or 1" and are not
+                          recorded (Section 4.4); 0 selects the default 1e-6 */
+} adasd_options;
+
+/*
+ * Scratch memory.  adasd_workspace_bytes writes to *bytes (host) the size needed by
+ * adasd_verify / adasd_draft_entropy for the given shape; the caller allocates it on
+ * the device (256-byte aligned), calls adasd_workspace_init once (it zeroes the
+ * arrival counters the kernels use; they clean up after themselves), and may reuse it
+ * for any smaller shape.  Calls that share a workspace must be ordered on one stream.
+ */
+int adasd_workspace_bytes(int B, int k_max, int V, adasd_dtype dt, size_t *bytes /* host */);
+int adasd_workspace_init(void *workspace, size_t ws_bytes, void *stream);
+
+/* Algorithm 1, initialisation: empty lists, T_G = 0.  `st` is a host struct of device pointers. */
+int adasd_state_init(const adasd_state *st, void *stream);
+
+/*
+ * Draft side (Section 4.3; generation loop of Algorithm 1).  For every active row b:
+ *   H_out[b]    = Shannon entropy of softmax(draft_logits[b, :]) in nats (Appendix A);
+ *   stop_out[b] = 1 if H_out[b] > T_G[b] (strict) or step + 1 >= k_max (window cap), else 0.
+ * draft_logits: [B, V] with `row_stride` elements between rows.  T_G, active, stop_out may be
+ * NULL (no threshold test / all rows active / no flag wanted).  Inactive rows are not read and
+ * get H_out = 0, stop_out = 0.  A non-finite row gives H_out = NaN and stop_out = 1.
+ */
+int adasd_draft_entropy(const void *draft_logits, adasd_dtype dt, int B, int V,
+                        int64_t row_stride, const float *T_G, const uint8_t *active, int step,
+                        int k_max, float *H_out, uint8_t *stop_out, void *workspace,
+                        size_t ws_bytes, void *stream);
+
+/*
+ * Verification of one round (Sections 2.1.3, 2.2, 4.4; verification loop of Algorithm 1).
+ * For sequence b with k_b = draft_len[b] candidates x_1..x_k (0-based position i below):
+ *   p_i = softmax(target_logits[b,i,:]),  q_i = softmax(draft_logits[b,i,:]);
+ *   H_p, H_q   : entropies (nats);   d_js : sqrt(D_JS(p_i||q_i) / ln 2);
+ *   p_accept   : P(A|d) from Gaussian KDEs of the two history lists with list-size priors;
+ *   base test  : u1 < min(1, p_i(x_i)/q_i(x_i));  Bayesian test per options.reject_rule on u2;
+ *   a candidate is rejected only if BOTH tests reject it; n_accept = index of the first
+ *   rejected candidate (k_b if none);
+ *   next_token : drawn from max(0, p_r - q_r) normalised at the first rejected position r
+ *                (from p_r if that has no mass), or from p_{k_b} (row k_b of the target, the
+ *                "bonus" row) when everything was accepted, by Gumbel-max over the vocabulary:
+ *                argmax_v ln w_v - ln(-ln u_v), lowest index on ties.
+ * Random numbers: Philox4x32-10 keyed by `seed`; counter = (block, position | stream<<16, round,
+ * sequence) where sequence = seq_id[b] (b if NULL) and round = round[b] (round0 if NULL).
+ *   acceptance uniforms of position i: block 0, stream 0, word 0 -> u1, word 1 -> u2,
+ *                                      u = ((word>>8) + 0.5) / 2^24;
+ *   Gumbel noise of element v        : block v>>2, stream 1, word v&3, u = (word + 0.5) / 2^32.
+ * Statistics are produced for every i < k_b (also after the first rejection); entries with
+ * i >= k_b are set to 0.  The state is only read; apply the round with adasd_update_thresholds.
+ */
+typedef struct {
+  /* inputs */
+  const void *target_logits;   /* [B, k_max+1, V] */
+  const void *draft_logits;    /* [B, k_max,   V] */
+  adasd_dtype dt;
+  int32_t B, k_max, V;
+  int64_t t_seq_stride, t_pos_stride; /* elements between sequences / positions of the target */
+  int64_t d_seq_stride, d_pos_stride; /* same for the draft */
+  const int32_t *draft_tokens; /* [B, k_max] */
+  const int32_t *draft_len;    /* [B] or NULL (= k_max everywhere) */
+  const adasd_state *state;    /* host struct; NULL = empty history (Bayesian test off) */
+  uint64_t seed;
+  const uint32_t *seq_id;      /* [B] or NULL */
+  const uint32_t *round;       /* [B] or NULL */
+  uint32_t round0;
+  /* outputs */
+  int32_t *n_accept;           /* [B]        0..k_b */
+  int32_t *next_token;         /* [B] */
+  float *H_p;                  /* [B, k_max] or NULL */
+  float *H_q;                  /* [B, k_max] */
+  float *d_js;                 /* [B, k_max] */
+  float *p_accept;             /* [B, k_max] or NULL */
+  uint8_t *accept_mask;        /* [B, k_max] or NULL; bit 0 base test, bit 1 Bayesian test */
+  uint32_t *status;            /* [B] */
+  void *workspace;
+  size_t ws_bytes;
+} adasd_verify_args;
+
+int adasd_verify(const adasd_verify_args *args /* host */, const adasd_options *opt /* host, may be NULL */,
+                 void *stream);
+
+/*
+ * Update step (Section 4.3, Section 4.4 last paragraph; update lines of Algorithm 1).
+ * For sequence b with r = n_accept[b]:
+ *   every accepted position i < r : append d_js[b,i] to L_D^A unless it is "exactly 0 or 1";
+ *   if r < k_b (a rejection)      : add H_q[b,r] to the rejected-entropy sum, append d_js[b,r] to
+ *                                    L_D^R under the same filter;
+ *   T_G[b] = mean rejected entropy (stays 0 while there is none).
+ * A full list drops the append and sets ADASD_ST_OVERFLOW in status[b] (status may be NULL; bits are
+ * OR-ed into it).  Non-finite H_q / d_js values are not recorded.
+ */
+int adasd_update_thresholds(const adasd_state *st /* host */, int k_max, const int32_t *n_accept,
+                            const int32_t *draft_len /* or NULL */, const float *H_q,
+                            const float *d_js, const adasd_options *opt /* host, may be NULL */,
+                            uint32_t *status /* or NULL */, void *stream);
+
+/*
+ * Optional kernel timing for benchmarks (host side only; not for production loops).
+ * adasd_profile_enable(n) creates n pairs of HIP events per kernel class and makes the entry points
+ * record them around their kernels; adasd_profile_read waits for the recorded events and returns the
+ * summed duration and launch count of one class since the last enable; adasd_profile_disable frees
+ * the events.  Kernel classes: 0 row statistics (normalisers + entropy), 1 JS distance, 2 decision,
+ * 3 token sampling, 4 state update, 5 draft entropy.
+ */
+int adasd_profile_enable(int max_launches);
+int adasd_profile_read(int kernel_class, double *total_ms /* host */, int *launches /* host */);
+int adasd_profile_disable(void);
+
+const char *adasd_strerror(int code);
+int adasd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

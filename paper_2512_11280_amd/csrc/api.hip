@@ -1,0 +1,374 @@
+// C ABI of libadasd: argument validation, workspace carving and kernel enqueue.
+#include <mutex>
+#include <vector>
+
+#include "internal.h"
+
+namespace adasd {
+
+namespace {
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// ---- optional kernel timing ----------------------------------------------------------------
+constexpr int kClasses = 6;
+struct Profiler {
+  std::mutex mu;
+  bool on = false;
+  int cap = 0;
+  std::vector<hipEvent_t> start[kClasses], stop[kClasses];
+  int used[kClasses] = {0, 0, 0, 0, 0, 0};
+} g_prof;
+
+struct Scope {   // records a start event now and a stop event at destruction
+  int cls;
+  hipStream_t st;
+  int slot = -1;
+  Scope(int c, hipStream_t s) : cls(c), st(s) {
+    if (!g_prof.on) return;
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    if (g_prof.used[cls] < g_prof.cap) {
+      slot = g_prof.used[cls]++;
+      (void)hipEventRecord(g_prof.start[cls][slot], st);
+    }
+  }
+  ~Scope() {
+    if (slot >= 0) (void)hipEventRecord(g_prof.stop[cls][slot], st);
+  }
+};
+
+}  // namespace
+
+size_t workspace_layout(int B, int K, Workspace* ws, void* base) {
+  const size_t rows = (size_t)B * (K > 0 ? (size_t)K * 2 : 1);
+  const size_t positions = (size_t)B * (K > 0 ? K : 1);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = off;
+    off = align_up(off + bytes, 256);
+    return at;
+  };
+  // Arrival counters sit at fixed offsets sized for the compiled limits, so that calls of different
+  // shapes sharing one workspace agree on where they are (they must read zero at entry).
+  const size_t o_t1 = take(65536 * sizeof(int32_t));
+  const size_t o_t2 = take(32768 * sizeof(int32_t));
+  const size_t o_t3 = take(32768 * sizeof(int32_t));
+  const size_t o_p1 = take(rows * kMaxSplit * sizeof(float4));
+  const size_t o_rows = take(rows * sizeof(RowResult));
+  const size_t o_p2 = take(positions * kMaxSplit * sizeof(float2));
+  const size_t o_plan = take((size_t)B * sizeof(SamplePlan));
+  const size_t o_p3 = take((size_t)B * kMaxSampleSplit * sizeof(Top2));
+  if (ws) {
+    char* p = static_cast<char*>(base);
+    ws->ticket1 = reinterpret_cast<int32_t*>(p + o_t1);
+    ws->ticket2 = reinterpret_cast<int32_t*>(p + o_t2);
+    ws->ticket3 = reinterpret_cast<int32_t*>(p + o_t3);
+    ws->part1 = reinterpret_cast<float4*>(p + o_p1);
+    ws->rows = reinterpret_cast<RowResult*>(p + o_rows);
+    ws->part2 = reinterpret_cast<float2*>(p + o_p2);
+    ws->plan = reinterpret_cast<SamplePlan*>(p + o_plan);
+    ws->part3 = reinterpret_cast<Top2*>(p + o_p3);
+    ws->bytes = off;
+  }
+  return off;
+}
+
+}  // namespace adasd
+
+using namespace adasd;
+
+extern "C" {
+
+int adasd_version(void) { return 100; }
+
+const char* adasd_strerror(int code) {
+  switch (code) {
+    case ADASD_OK: return "ok";
+    case ADASD_ERR_INVALID_ARG: return "invalid argument";
+    case ADASD_ERR_MISALIGNED: return "pointer below the natural alignment of its element type";
+    case ADASD_ERR_UNSUPPORTED: return "option value not supported by this build";
+    case ADASD_ERR_WORKSPACE: return "workspace missing or too small";
+    case ADASD_ERR_CAPACITY: return "size beyond a compiled limit";
+    case ADASD_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error code";
+  }
+}
+
+static int check_shape(int B, int k_max, int V, int dt) {
+  if (B < 0 || k_max < 0 || V < 1) return ADASD_ERR_INVALID_ARG;
+  if (dt != ADASD_F32 && dt != ADASD_BF16) return ADASD_ERR_INVALID_ARG;
+  if (k_max > ADASD_MAX_K || V > ADASD_MAX_V) return ADASD_ERR_CAPACITY;
+  if ((int64_t)B * (k_max > 0 ? k_max : 1) * 2 > 65535) return ADASD_ERR_CAPACITY;
+  return ADASD_OK;
+}
+
+int adasd_workspace_bytes(int B, int k_max, int V, adasd_dtype dt, size_t* bytes) {
+  if (!bytes) return ADASD_ERR_INVALID_ARG;
+  int rc = check_shape(B, k_max, V, (int)dt);
+  if (rc) return rc;
+  // large enough for a verify call of this shape and for draft-entropy calls with the same B
+  *bytes = workspace_layout(B, k_max > 0 ? k_max : 1, nullptr, nullptr);
+  return ADASD_OK;
+}
+
+int adasd_workspace_init(void* workspace, size_t ws_bytes, void* stream) {
+  if (!workspace || ws_bytes == 0) return ADASD_ERR_WORKSPACE;
+  if (!aligned_to(workspace, 256)) return ADASD_ERR_MISALIGNED;
+  return launch_zero(workspace, ws_bytes, (hipStream_t)stream) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
+}
+
+static int check_state(const adasd_state* st) {
+  if (!st) return ADASD_ERR_INVALID_ARG;
+  if (st->B < 0 || st->cap < 0) return ADASD_ERR_INVALID_ARG;
+  if (st->B == 0) return ADASD_OK;
+  if (!st->T_G || !st->ent_sum || !st->ent_cnt || !st->nA || !st->nR) return ADASD_ERR_INVALID_ARG;
+  if (st->cap > 0 && (!st->LA || !st->LR)) return ADASD_ERR_INVALID_ARG;
+  if (!aligned_to(st->T_G, 4) || !aligned_to(st->ent_sum, 8) || !aligned_to(st->ent_cnt, 4) ||
+      !aligned_to(st->LA, 4) || !aligned_to(st->LR, 4) || !aligned_to(st->nA, 4) ||
+      !aligned_to(st->nR, 4))
+    return ADASD_ERR_MISALIGNED;
+  return ADASD_OK;
+}
+
+static UpdateArgs state_args(const adasd_state* st) {
+  UpdateArgs u{};
+  u.B = st->B;
+  u.cap = st->cap;
+  u.T_G = st->T_G;
+  u.ent_sum = st->ent_sum;
+  u.ent_cnt = st->ent_cnt;
+  u.LA = st->LA;
+  u.LR = st->LR;
+  u.nA = st->nA;
+  u.nR = st->nR;
+  return u;
+}
+
+int adasd_state_init(const adasd_state* st, void* stream) {
+  int rc = check_state(st);
+  if (rc) return rc;
+  UpdateArgs u = state_args(st);
+  return launch_state_init(u, (hipStream_t)stream) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
+}
+
+int adasd_draft_entropy(const void* draft_logits, adasd_dtype dt, int B, int V, int64_t row_stride,
+                        const float* T_G, const uint8_t* active, int step, int k_max, float* H_out,
+                        uint8_t* stop_out, void* workspace, size_t ws_bytes, void* stream) {
+  int rc = check_shape(B, 0, V, (int)dt);
+  if (rc) return rc;
+  if (B == 0) return ADASD_OK;
+  if (!draft_logits || !H_out || row_stride < V || step < 0 || k_max < 1) return ADASD_ERR_INVALID_ARG;
+  const size_t es = dt == ADASD_BF16 ? 2 : 4;
+  if (!aligned_to(draft_logits, es) || !aligned_to(H_out, 4) || !aligned_to(T_G, 4))
+    return ADASD_ERR_MISALIGNED;
+  if (!workspace) return ADASD_ERR_WORKSPACE;
+  if (!aligned_to(workspace, 256)) return ADASD_ERR_MISALIGNED;
+  Workspace ws;
+  if (workspace_layout(B, 0, &ws, workspace) > ws_bytes) return ADASD_ERR_WORKSPACE;
+
+  RowMap map{};
+  map.base[0] = static_cast<const char*>(draft_logits);
+  map.base[1] = nullptr;
+  map.seq_stride[0] = row_stride;
+  map.active = active;
+  map.K = 0;
+  map.B = B;
+  map.V = V;
+  DraftOut dout{T_G, H_out, stop_out, step + 1 >= k_max ? 1 : 0};
+  VerifyOut vout{nullptr, nullptr, nullptr};
+  hipStream_t st = (hipStream_t)stream;
+  const int S = pick_split(B, V, (int)dt);
+  Scope sc(5, st);
+  return launch_rowstats(map, (int)dt, B, S, ws, vout, dout, st) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
+}
+
+int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* stream) {
+  if (!a) return ADASD_ERR_INVALID_ARG;
+  adasd_options opt{};
+  if (opt_in) opt = *opt_in;
+  int rc = check_shape(a->B, a->k_max, a->V, (int)a->dt);
+  if (rc) return rc;
+  if (opt.base_test != 0) return ADASD_ERR_UNSUPPORTED;
+  if (opt.reject_rule != 0 && opt.reject_rule != 1) return ADASD_ERR_INVALID_ARG;
+  if (opt.bw_rule != 0 && opt.bw_rule != 1) return ADASD_ERR_INVALID_ARG;
+  if (a->B == 0) return ADASD_OK;
+  const int B = a->B, K = a->k_max, V = a->V;
+  if (!a->target_logits || !a->n_accept || !a->next_token || !a->status) return ADASD_ERR_INVALID_ARG;
+  if (K > 0 && (!a->draft_logits || !a->draft_tokens || !a->H_q || !a->d_js))
+    return ADASD_ERR_INVALID_ARG;
+  if (a->t_pos_stride < V || a->t_seq_stride < (int64_t)(K + 1) * V) return ADASD_ERR_INVALID_ARG;
+  if (K > 0 && (a->d_pos_stride < V || a->d_seq_stride < (int64_t)K * V)) return ADASD_ERR_INVALID_ARG;
+  const size_t es = a->dt == ADASD_BF16 ? 2 : 4;
+  if (!aligned_to(a->target_logits, es) || !aligned_to(a->draft_logits, es) ||
+      !aligned_to(a->draft_tokens, 4) || !aligned_to(a->draft_len, 4) || !aligned_to(a->seq_id, 4) ||
+      !aligned_to(a->round, 4) || !aligned_to(a->n_accept, 4) || !aligned_to(a->next_token, 4) ||
+      !aligned_to(a->H_p, 4) || !aligned_to(a->H_q, 4) || !aligned_to(a->d_js, 4) ||
+      !aligned_to(a->p_accept, 4) || !aligned_to(a->status, 4))
+    return ADASD_ERR_MISALIGNED;
+  if (a->state) {
+    rc = check_state(a->state);
+    if (rc) return rc;
+    if (a->state->B < B) return ADASD_ERR_INVALID_ARG;
+  }
+  if (!a->workspace) return ADASD_ERR_WORKSPACE;
+  if (!aligned_to(a->workspace, 256)) return ADASD_ERR_MISALIGNED;
+  Workspace ws;
+  if (workspace_layout(B, K > 0 ? K : 1, &ws, a->workspace) > a->ws_bytes) return ADASD_ERR_WORKSPACE;
+
+  hipStream_t st = (hipStream_t)stream;
+  RowMap map{};
+  map.base[0] = static_cast<const char*>(a->target_logits);
+  map.base[1] = static_cast<const char*>(a->draft_logits);
+  map.seq_stride[0] = a->t_seq_stride;
+  map.pos_stride[0] = a->t_pos_stride;
+  map.seq_stride[1] = a->d_seq_stride;
+  map.pos_stride[1] = a->d_pos_stride;
+  map.draft_len = a->draft_len;
+  map.active = nullptr;
+  map.K = K;
+  map.B = B;
+  map.V = V;
+
+  VerifyOut vout{a->H_p, a->H_q, a->d_js};
+  DraftOut dout{nullptr, nullptr, nullptr, 0};
+  if (K > 0) {
+    const int rows = B * K * 2;
+    const int S = pick_split(rows, V, (int)a->dt);
+    {
+      Scope sc(0, st);
+      if (launch_rowstats(map, (int)a->dt, rows, S, ws, vout, dout, st) != hipSuccess) return ADASD_ERR_HIP;
+    }
+    {
+      Scope sc(1, st);
+      if (launch_jsd(map, (int)a->dt, S, ws, vout, st) != hipSuccess) return ADASD_ERR_HIP;
+    }
+  }
+
+  DecideArgs d{};
+  d.map = map;
+  d.dt = (int)a->dt;
+  d.draft_tokens = a->draft_tokens;
+  if (a->state) {
+    d.cap = a->state->cap;
+    d.LA = a->state->LA;
+    d.LR = a->state->LR;
+    d.nA = a->state->nA;
+    d.nR = a->state->nR;
+  }
+  d.seed_lo = (uint32_t)a->seed;
+  d.seed_hi = (uint32_t)(a->seed >> 32);
+  d.seq_id = a->seq_id;
+  d.round = a->round;
+  d.round0 = a->round0;
+  d.reject_rule = opt.reject_rule;
+  d.kde_min_n = opt.kde_min_n;
+  d.bw_rule = opt.bw_rule;
+  d.relaxed_off = opt.relaxed_off;
+  d.n_accept = a->n_accept;
+  d.H_p = a->H_p;
+  d.H_q = a->H_q;
+  d.d_js = a->d_js;
+  d.p_accept = a->p_accept;
+  d.accept_mask = a->accept_mask;
+  d.status = a->status;
+  {
+    Scope sc(2, st);
+    if (launch_decide(d, ws, st) != hipSuccess) return ADASD_ERR_HIP;
+  }
+
+  SampleArgs s{};
+  s.map = map;
+  s.dt = (int)a->dt;
+  s.seed_lo = d.seed_lo;
+  s.seed_hi = d.seed_hi;
+  s.seq_id = a->seq_id;
+  s.round = a->round;
+  s.round0 = a->round0;
+  s.next_token = a->next_token;
+  s.status = a->status;
+  int S3 = pick_split(B * 8, V, (int)a->dt);
+  if (S3 > kMaxSampleSplit) S3 = kMaxSampleSplit;
+  {
+    Scope sc(3, st);
+    if (launch_sample(s, S3, ws, st) != hipSuccess) return ADASD_ERR_HIP;
+  }
+  return ADASD_OK;
+}
+
+int adasd_update_thresholds(const adasd_state* st, int k_max, const int32_t* n_accept,
+                            const int32_t* draft_len, const float* H_q, const float* d_js,
+                            const adasd_options* opt, uint32_t* status, void* stream) {
+  int rc = check_state(st);
+  if (rc) return rc;
+  if (k_max < 0) return ADASD_ERR_INVALID_ARG;
+  if (k_max > ADASD_MAX_K) return ADASD_ERR_CAPACITY;
+  if (st->B == 0) return ADASD_OK;
+  if (!n_accept || (k_max > 0 && (!H_q || !d_js))) return ADASD_ERR_INVALID_ARG;
+  if (!aligned_to(n_accept, 4) || !aligned_to(draft_len, 4) || !aligned_to(H_q, 4) ||
+      !aligned_to(d_js, 4) || !aligned_to(status, 4))
+    return ADASD_ERR_MISALIGNED;
+  UpdateArgs u = state_args(st);
+  u.K = k_max;
+  u.n_accept = n_accept;
+  u.draft_len = draft_len;
+  u.H_q = H_q;
+  u.d_js = d_js;
+  u.d_eps = (opt && opt->d_eps > 0.f) ? opt->d_eps : 1e-6f;
+  u.status = status;
+  hipStream_t s = (hipStream_t)stream;
+  Scope sc(4, s);
+  return launch_update(u, s) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
+}
+
+int adasd_profile_enable(int max_launches) {
+  if (max_launches < 1) return ADASD_ERR_INVALID_ARG;
+  adasd_profile_disable();
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  for (int c = 0; c < kClasses; ++c) {
+    g_prof.start[c].resize(max_launches);
+    g_prof.stop[c].resize(max_launches);
+    for (int i = 0; i < max_launches; ++i) {
+      if (hipEventCreate(&g_prof.start[c][i]) != hipSuccess) return ADASD_ERR_HIP;
+      if (hipEventCreate(&g_prof.stop[c][i]) != hipSuccess) return ADASD_ERR_HIP;
+    }
+    g_prof.used[c] = 0;
+  }
+  g_prof.cap = max_launches;
+  g_prof.on = true;
+  return ADASD_OK;
+}
+
+int adasd_profile_read(int kernel_class, double* total_ms, int* launches) {
+  if (kernel_class < 0 || kernel_class >= kClasses || !total_ms || !launches) return ADASD_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  double sum = 0.0;
+  const int n = g_prof.used[kernel_class];
+  for (int i = 0; i < n; ++i) {
+    if (hipEventSynchronize(g_prof.stop[kernel_class][i]) != hipSuccess) return ADASD_ERR_HIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, g_prof.start[kernel_class][i], g_prof.stop[kernel_class][i]) != hipSuccess)
+      return ADASD_ERR_HIP;
+    sum += ms;
+  }
+  *total_ms = sum;
+  *launches = n;
+  return ADASD_OK;
+}
+
+int adasd_profile_disable(void) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  for (int c = 0; c < kClasses; ++c) {
+    for (auto e : g_prof.start[c]) (void)hipEventDestroy(e);
+    for (auto e : g_prof.stop[c]) (void)hipEventDestroy(e);
+    g_prof.start[c].clear();
+    g_prof.stop[c].clear();
+    g_prof.used[c] = 0;
+  }
+  g_prof.cap = 0;
+  g_prof.on = false;
+  return ADASD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,117 @@
+// Host-side declarations shared by the translation units of libadasd.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/adasd.h"
+#include "device_common.h"
+
+namespace adasd {
+
+constexpr int kMaxSplit = 64;        // vocabulary slices per row (statistics kernels)
+constexpr int kMaxSampleSplit = 128; // vocabulary slices per sequence (sampling kernel)
+
+// Where the rows of one call live.  which = 0: target, 1: draft.
+struct RowMap {
+  const char* base[2];
+  int64_t seq_stride[2], pos_stride[2];  // elements
+  const int32_t* draft_len;              // [B] or null
+  const uint8_t* active;                 // [B] or null (draft-entropy mode)
+  int32_t K;                             // k_max; 0 selects draft-entropy mode (one row per sequence)
+  int32_t B, V;
+};
+
+struct Workspace {
+  float4* part1;      // [rows][kMaxSplit]   (m, s, u, -) partial log-sum-exp states
+  int32_t* ticket1;   // [rows]              arrival counters, zero between calls
+  RowResult* rows;    // [rows]
+  float2* part2;      // [positions][kMaxSplit] partial KL sums (p side, q side), log2 units
+  int32_t* ticket2;   // [positions]
+  SamplePlan* plan;   // [B]
+  Top2* part3;        // [B][kMaxSampleSplit]
+  int32_t* ticket3;   // [B]
+  size_t bytes;
+};
+
+size_t workspace_layout(int B, int K, Workspace* ws, void* base);
+
+struct DraftOut {     // draft-entropy epilogue
+  const float* T_G;
+  float* H_out;
+  uint8_t* stop_out;
+  int32_t force_stop; // step + 1 >= k_max
+};
+
+struct VerifyOut {
+  float* H_p;
+  float* H_q;
+  float* d_js;
+};
+
+int pick_split(int rows, int V, int dt);
+
+hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Workspace& ws,
+                           const VerifyOut& vout, const DraftOut& dout, hipStream_t st);
+hipError_t launch_jsd(const RowMap& map, int dt, int S, const Workspace& ws, const VerifyOut& vout,
+                      hipStream_t st);
+
+struct DecideArgs {
+  RowMap map;
+  int32_t dt;
+  const int32_t* draft_tokens;
+  // state (device pointers, may be null)
+  int32_t cap;
+  const float* LA;
+  const float* LR;
+  const int32_t* nA;
+  const int32_t* nR;
+  uint32_t seed_lo, seed_hi;
+  const uint32_t* seq_id;
+  const uint32_t* round;
+  uint32_t round0;
+  int32_t reject_rule, kde_min_n, bw_rule, relaxed_off;
+  // outputs
+  int32_t* n_accept;
+  float* H_p;
+  float* H_q;
+  float* d_js;
+  float* p_accept;
+  uint8_t* accept_mask;
+  uint32_t* status;
+};
+hipError_t launch_decide(const DecideArgs& a, const Workspace& ws, hipStream_t st);
+
+struct SampleArgs {
+  RowMap map;
+  int32_t dt;
+  uint32_t seed_lo, seed_hi;
+  const uint32_t* seq_id;
+  const uint32_t* round;
+  uint32_t round0;
+  int32_t* next_token;
+  uint32_t* status;
+};
+hipError_t launch_sample(const SampleArgs& a, int S, const Workspace& ws, hipStream_t st);
+
+struct UpdateArgs {
+  int32_t B, K, cap;
+  float* T_G;
+  double* ent_sum;
+  int32_t* ent_cnt;
+  float* LA;
+  float* LR;
+  int32_t* nA;
+  int32_t* nR;
+  const int32_t* n_accept;
+  const int32_t* draft_len;
+  const float* H_q;
+  const float* d_js;
+  float d_eps;
+  uint32_t* status;
+};
+hipError_t launch_update(const UpdateArgs& a, hipStream_t st);
+hipError_t launch_state_init(const UpdateArgs& a, hipStream_t st);
+hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
+
+}  // namespace adasd

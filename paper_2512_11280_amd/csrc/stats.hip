@@ -1,0 +1,274 @@
+// Vocabulary-wide statistics: softmax normalisers + Shannon entropy of every row (Appendix A of
+// the paper) and the Jensen-Shannon distance of every (target, draft) row pair (Section 2.2).
+//
+// Two-kernel split-vocabulary form: each row is cut into S slices, one workgroup per slice;
+// partial results meet in the workspace and the workgroup that arrives last at a row's counter
+// folds them (fixed butterfly order, so results do not depend on arrival order).
+#include "internal.h"
+
+namespace adasd {
+
+namespace {
+
+struct RowRef {
+  const char* ptr;
+  int b, i, which;
+  bool active;
+};
+
+template <int DT>
+__device__ __forceinline__ RowRef locate_row(const RowMap& map, int rho) {
+  RowRef r;
+  if (map.K > 0) {
+    r.which = rho & 1;
+    int pos = rho >> 1;
+    r.b = pos / map.K;
+    r.i = pos - r.b * map.K;
+    int kb = map.K;
+    if (map.draft_len) kb = min(max(map.draft_len[r.b], 0), map.K);
+    r.active = r.i < kb;
+  } else {
+    r.which = 0;
+    r.b = rho;
+    r.i = 0;
+    r.active = map.active ? (map.active[rho] != 0) : true;
+  }
+  int64_t off = (int64_t)r.b * map.seq_stride[r.which] + (int64_t)r.i * map.pos_stride[r.which];
+  r.ptr = map.base[r.which] + off * Elem<DT>::bytes;
+  return r;
+}
+
+__device__ __forceinline__ bool aligned16(const void* p) {
+  return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
+}
+
+// One element of the row joins the running state (reference raised first if needed).
+__device__ __forceinline__ void lse_push(Lse& st, float z) {
+  lse_raise(st, z * kLog2e);
+  lse_add(st, z);
+}
+
+template <int DT>
+__device__ __forceinline__ void lse_push_vec(Lse& st, const uint4& q) {
+  constexpr int N = Elem<DT>::per_vec;
+  float z[N];
+  unpack<DT>(q, z);
+  float vmax = z[0];
+#pragma unroll
+  for (int e = 1; e < N; ++e) vmax = fmaxf(vmax, z[e]);
+  lse_raise(st, vmax * kLog2e);   // NaN-free max: a NaN logit surfaces through lse_add instead
+#pragma unroll
+  for (int e = 0; e < N; ++e) lse_add(st, z[e]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pass 1: partial (m, s, u) of one slice of one row; last arrival finalises lse and entropy.
+// ---------------------------------------------------------------------------------------------
+template <int DT>
+__global__ void __launch_bounds__(kBlock)
+k_rowstats(RowMap map, int S, Workspace ws, VerifyOut vout, DraftOut dout) {
+  constexpr int EPV = Elem<DT>::per_vec;
+  const int rho = blockIdx.y, s = blockIdx.x, tid = threadIdx.x;
+  const RowRef r = locate_row<DT>(map, rho);
+  if (!r.active) {
+    if (map.K == 0 && s == 0 && tid == 0) {
+      dout.H_out[r.b] = 0.f;
+      if (dout.stop_out) dout.stop_out[r.b] = 0;
+    }
+    return;
+  }
+  const int V = map.V;
+  Lse st = lse_empty();
+  if (aligned16(r.ptr)) {
+    const int nv = V / EPV;
+    const int v0 = (int)(((int64_t)s * nv) / S), v1 = (int)(((int64_t)(s + 1) * nv) / S);
+    const uint4* vec = reinterpret_cast<const uint4*>(r.ptr);
+    for (int j = v0 + tid; j < v1; j += kBlock) lse_push_vec<DT>(st, vec[j]);
+    if (s == S - 1 && tid == 0)
+      for (int v = nv * EPV; v < V; ++v) lse_push(st, load_elem<DT>(r.ptr, v));
+  } else {
+    const int e0 = (int)(((int64_t)s * V) / S), e1 = (int)(((int64_t)(s + 1) * V) / S);
+    for (int v = e0 + tid; v < e1; v += kBlock) lse_push(st, load_elem<DT>(r.ptr, v));
+  }
+
+  __shared__ Lse sh[kWaves];
+  __shared__ int sh_last;
+  st = wave_reduce(st);
+  const int lane = tid & 63, wave = tid >> 6;
+  if (lane == 0) sh[wave] = st;
+  __syncthreads();
+  if (tid == 0) {
+    Lse t = sh[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) t = lse_merge(t, sh[w]);
+    float* dst = reinterpret_cast<float*>(&ws.part1[(size_t)rho * kMaxSplit + s]);
+    st_agent(dst, t.m);
+    st_agent(dst + 1, t.s);
+    st_agent(dst + 2, t.u);
+    publish_barrier();
+    int ticket = atomicAdd(&ws.ticket1[rho], 1);
+    sh_last = (ticket == S - 1);
+  }
+  __syncthreads();
+  if (!sh_last || wave != 0) return;
+
+  Lse t = lse_empty();
+  if (lane < S) {
+    const float* p = reinterpret_cast<const float*>(&ws.part1[(size_t)rho * kMaxSplit + lane]);
+    t.m = ld_agent(p);
+    t.s = ld_agent(p + 1);
+    t.u = ld_agent(p + 2);
+  }
+  t = wave_reduce(t);
+  if (lane != 0) return;
+  const bool ok = (t.s > 0.f) && (t.s < INFINITY) && (fabsf(t.u) < INFINITY) && (t.m > kNegHuge) &&
+                  (t.m < INFINITY);
+  RowResult res;
+  if (ok) {
+    double l2s = log2((double)t.s);
+    res.lse2 = (double)t.m + l2s;
+    res.H = (float)(kLn2 * (l2s - (double)t.u / (double)t.s));
+    res.bad = 0;
+  } else {
+    res.lse2 = NAN;
+    res.H = NAN;
+    res.bad = 1;
+  }
+  ws.rows[rho] = res;
+  if (map.K > 0) {
+    float* H = r.which == 0 ? vout.H_p : vout.H_q;
+    if (H) H[(size_t)r.b * map.K + r.i] = res.H;
+  } else {
+    dout.H_out[r.b] = res.H;
+    if (dout.stop_out) {
+      bool over = dout.T_G ? (res.H > dout.T_G[r.b]) : false;
+      dout.stop_out[r.b] = (uint8_t)(over || dout.force_stop || res.bad);
+    }
+  }
+  __hip_atomic_store(&ws.ticket1[rho], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pass 2: JS divergence.  Per element, with b = max(p,q), r = min(p,q)/max(p,q) = 2^-|delta| and
+// delta = log2 q - log2 p,
+//     p log2(p/m) + q log2(q/m) = b * ( r * log2 r - (1 + r) * log2((1 + r)/2) ),   m = (p+q)/2,
+// which is non-negative, symmetric in (p,q), never overflows (r <= 1), and keeps every logarithm
+// at magnitude <= 1 so the hardware log's absolute error stays at the 1e-7 level even when the
+// probabilities themselves are 2^-17.  delta is formed from the exact logit difference.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void jsd_push(float zp, float zq, float cp, float cq, float dc, float& acc) {
+  float yp = fmaf(zp, kLog2e, -cp), yq = fmaf(zq, kLog2e, -cq);   // log2 p, log2 q
+  float b = ex2(fmaxf(yp, yq));
+  float delta = fmaf(zq - zp, kLog2e, -dc);
+  float nd = fmaxf(-fabsf(delta), -126.0f);   // masked logits (delta = +-inf or NaN) end up at r = 2^-126
+  float r = ex2(nd);
+  float h = fmaf(r, 0.5f, 0.5f);
+  float t = fmaf(-2.0f, h * lg2(h), r * nd);
+  acc = fmaf(b, t, acc);
+}
+
+template <int DT>
+__global__ void __launch_bounds__(kBlock)
+k_jsd(RowMap map, int S, Workspace ws, VerifyOut vout) {
+  constexpr int EPV = Elem<DT>::per_vec;
+  const int pos = blockIdx.y, s = blockIdx.x, tid = threadIdx.x;
+  const RowRef rp = locate_row<DT>(map, 2 * pos), rq = locate_row<DT>(map, 2 * pos + 1);
+  if (!rp.active) return;
+  const RowResult resp = ws.rows[2 * pos], resq = ws.rows[2 * pos + 1];
+  if (resp.bad || resq.bad) {
+    if (s == 0 && tid == 0) vout.d_js[pos] = NAN;
+    return;
+  }
+  const float cp = (float)resp.lse2, cq = (float)resq.lse2;
+  const float dc = (float)(resq.lse2 - resp.lse2);
+  const int V = map.V;
+  float acc = 0.f;
+  if (aligned16(rp.ptr) && aligned16(rq.ptr)) {
+    const int nv = V / EPV;
+    const int v0 = (int)(((int64_t)s * nv) / S), v1 = (int)(((int64_t)(s + 1) * nv) / S);
+    const uint4* vp = reinterpret_cast<const uint4*>(rp.ptr);
+    const uint4* vq = reinterpret_cast<const uint4*>(rq.ptr);
+    for (int j = v0 + tid; j < v1; j += kBlock) {
+      float zp[EPV], zq[EPV];
+      unpack<DT>(vp[j], zp);
+      unpack<DT>(vq[j], zq);
+#pragma unroll
+      for (int e = 0; e < EPV; ++e) jsd_push(zp[e], zq[e], cp, cq, dc, acc);
+    }
+    if (s == S - 1 && tid == 0)
+      for (int v = nv * EPV; v < V; ++v)
+        jsd_push(load_elem<DT>(rp.ptr, v), load_elem<DT>(rq.ptr, v), cp, cq, dc, acc);
+  } else {
+    const int e0 = (int)(((int64_t)s * V) / S), e1 = (int)(((int64_t)(s + 1) * V) / S);
+    for (int v = e0 + tid; v < e1; v += kBlock)
+      jsd_push(load_elem<DT>(rp.ptr, v), load_elem<DT>(rq.ptr, v), cp, cq, dc, acc);
+  }
+
+  __shared__ float sha[kWaves];
+  __shared__ int sh_last;
+  acc = wave_sum(acc);
+  const int lane = tid & 63, wave = tid >> 6;
+  if (lane == 0) sha[wave] = acc;
+  __syncthreads();
+  if (tid == 0) {
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) t += sha[w];
+    st_agent(reinterpret_cast<float*>(&ws.part2[(size_t)pos * kMaxSplit + s]), t);
+    publish_barrier();
+    int ticket = atomicAdd(&ws.ticket2[pos], 1);
+    sh_last = (ticket == S - 1);
+  }
+  __syncthreads();
+  if (!sh_last || wave != 0) return;
+
+  double A = 0.0;
+  if (lane < S) A = (double)ld_agent(reinterpret_cast<const float*>(&ws.part2[(size_t)pos * kMaxSplit + lane]));
+  A = wave_sum(A);
+  if (lane != 0) return;
+  // The weights b were formed with the float roundings cp, cq of the normalisers, i.e. they are
+  // p(1+a), q(1+a') with a = ln2 (lse2_p - cp); the sum scales by 1 + (a+a')/2 to first order.
+  const double a = kLn2 * (resp.lse2 - (double)cp), a2 = kLn2 * (resq.lse2 - (double)cq);
+  double D = 0.5 * A * (1.0 - 0.5 * (a + a2));   // bits
+  D = fmin(fmax(D, 0.0), 1.0);
+  vout.d_js[pos] = (float)sqrt(D);
+  __hip_atomic_store(&ws.ticket2[pos], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+}  // namespace
+
+int pick_split(int rows, int V, int dt) {
+  const int epv = dt == ADASD_BF16 ? 8 : 4;
+  const int nv = V / epv;
+  int S = (4096 + rows - 1) / (rows > 0 ? rows : 1);
+  int cap = nv / kBlock;            // at least one vector per thread and slice
+  if (S > cap) S = cap;
+  if (S > kMaxSplit) S = kMaxSplit;
+  if (S < 1) S = 1;
+  return S;
+}
+
+hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Workspace& ws,
+                           const VerifyOut& vout, const DraftOut& dout, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  dim3 grid(S, rows), block(kBlock);
+  if (dt == ADASD_BF16)
+    hipLaunchKernelGGL(k_rowstats<ADASD_BF16>, grid, block, 0, st, map, S, ws, vout, dout);
+  else
+    hipLaunchKernelGGL(k_rowstats<ADASD_F32>, grid, block, 0, st, map, S, ws, vout, dout);
+  return hipGetLastError();
+}
+
+hipError_t launch_jsd(const RowMap& map, int dt, int S, const Workspace& ws, const VerifyOut& vout,
+                      hipStream_t st) {
+  const int positions = map.B * map.K;
+  if (positions <= 0) return hipSuccess;
+  dim3 grid(S, positions), block(kBlock);
+  if (dt == ADASD_BF16)
+    hipLaunchKernelGGL(k_jsd<ADASD_BF16>, grid, block, 0, st, map, S, ws, vout);
+  else
+    hipLaunchKernelGGL(k_jsd<ADASD_F32>, grid, block, 0, st, map, S, ws, vout);
+  return hipGetLastError();
+}
+
+}  // namespace adasd

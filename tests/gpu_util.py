@@ -1,0 +1,108 @@
+"""Shared helpers of the GPU parity tests: run the HIP library and the CPU oracle on the same
+seeded inputs and compare element by element, with the tolerances of the build's contract:
+
+  * entropies and JS distance: |gpu - oracle| <= 1e-5 |oracle| + 1e-6; for very small distances
+    the bound is taken on the divergence D = d^2 instead: |D_gpu - D_oracle| <= 1e-5 D + 2e-7
+    (the kernels form D from float probabilities of total mass 1, so D carries an absolute
+    uncertainty of a few float ulps of 1 -- about 2e-8 measured -- whatever its size)
+  * accepted lengths and sampled token ids: bit-exact
+  * an acceptance bit may differ only where the deciding statistic lies within 1e-5 of its
+    threshold (ln u1 vs the log ratio; u2 vs P(A|d)); every such flip is counted and the
+    sequence's downstream integers are then not compared.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+RTOL, ATOL = 1e-5, 1e-6
+D_FLOOR = 2e-7
+FLIP_BAND = 1e-5
+PA_ATOL = 2e-5          # posterior moves by dP/dd * 1e-5*d; slope of the KDE ratio can reach ~1/h
+
+
+def to_dev(x):
+    return None if x is None else x.cuda()
+
+
+def state_to_device(am, host_state, B, cap):
+    st = am.State(B, cap)
+    st.load({k: host_state[k] for k in ("T_G", "ent_sum", "ent_cnt", "LA", "LR", "nA", "nR")})
+    return st
+
+
+def run_gpu(am, batch, options=None, seq_id=None, rounds=None, ws=None):
+    B, K, V = batch.B, batch.k, batch.V
+    ws = ws or am.Workspace(B, max(K, 1), V, batch.target.dtype)
+    cap = batch.state["LA"].shape[1]
+    st = state_to_device(am, batch.state, B, cap)
+    sid = None if seq_id is None else torch.tensor(np.asarray(seq_id, dtype=np.uint32).view(np.int32)).cuda()
+    rnd = None if rounds is None else torch.tensor(np.asarray(rounds, dtype=np.uint32).view(np.int32)).cuda()
+    out = am.verify(batch.target.cuda(), batch.draft.cuda(), batch.draft_tokens.cuda(), ws, state=st,
+                    draft_len=to_dev(batch.draft_len), seed=batch.seed, seq_id=sid, rounds=rnd,
+                    round0=batch.round0, options=options)
+    torch.cuda.synchronize()
+    return out, st, ws
+
+
+def run_oracle(oracle, batch, options=None, seq_id=None, rounds=None):
+    kw = {}
+    if options is not None:
+        kw = dict(reject_rule=options.reject_rule, kde_min_n=options.kde_min_n,
+                  bw_rule=options.bw_rule, relaxed_off=options.relaxed_off)
+    s = batch.state
+    return oracle.verify(batch.target, batch.draft, batch.draft_tokens.numpy(),
+                         draft_len=None if batch.draft_len is None else batch.draft_len.numpy(),
+                         LA=s["LA"], LR=s["LR"], nA=s["nA"], nR=s["nR"], seed=batch.seed,
+                         seq_id=seq_id, rounds=rounds, round0=batch.round0, **kw)
+
+
+def close(gpu, ref, rtol=RTOL, atol=ATOL):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    both_nan = np.isnan(gpu) & np.isnan(ref)
+    ok = np.abs(gpu - ref) <= rtol * np.abs(ref) + atol
+    return ok | both_nan
+
+
+def compare_verify(gpu, ref, info_bits=16):
+    """Returns a report dict; raises AssertionError on any disagreement outside the contract."""
+    g = {k: getattr(gpu, k).cpu().numpy() for k in
+         ("n_accept", "next_token", "H_p", "H_q", "d_js", "p_accept", "accept_mask", "status")}
+    rep = dict(flips=0, exact_path=int(((g["status"] & info_bits) != 0).sum()), seq_skipped=0)
+    for name in ("H_p", "H_q", "d_js"):
+        ok = close(g[name], ref[name])
+        if name == "d_js":
+            ok |= close(g[name].astype(np.float64) ** 2, ref[name] ** 2, rtol=RTOL, atol=D_FLOOR)
+        if not ok.all():
+            bad = np.argwhere(~ok)[0]
+            raise AssertionError(f"{name} mismatch at {tuple(bad)}: gpu {g[name][tuple(bad)]!r} "
+                                 f"oracle {ref[name][tuple(bad)]!r}")
+    okp = close(g["p_accept"], ref["p_accept"], rtol=0.0, atol=PA_ATOL)
+    assert okp.all(), f"p_accept mismatch: max diff {np.nanmax(np.abs(g['p_accept'] - ref['p_accept']))}"
+    rep["max_rel_H"] = float(np.nanmax(np.abs(g["H_q"] - ref["H_q"]) / np.maximum(np.abs(ref["H_q"]), 1e-30),
+                                       initial=0.0))
+    rep["max_rel_d"] = float(np.nanmax(np.abs(g["d_js"] - ref["d_js"]) / np.maximum(np.abs(ref["d_js"]), 1e-30),
+                                       initial=0.0))
+
+    B = g["n_accept"].shape[0]
+    gm, rm = g["accept_mask"], ref["accept_mask"]
+    flipped_seq = np.zeros(B, dtype=bool)
+    for bit, margin in ((1, ref["base_margin"]), (2, ref["relaxed_margin"])):
+        diff = (gm & bit) != (rm & bit)
+        if diff.any():
+            assert (np.abs(margin[diff]) <= FLIP_BAND).all(), \
+                f"acceptance bit {bit} differs outside the 1e-5 band: margins {margin[diff]}"
+            rep["flips"] += int(diff.sum())
+            flipped_seq |= diff.any(axis=1)
+    rep["seq_skipped"] = int(flipped_seq.sum())
+    keep = ~flipped_seq
+    assert np.array_equal(g["n_accept"][keep], ref["n_accept"][keep]), \
+        (g["n_accept"][keep], ref["n_accept"][keep])
+    if not np.array_equal(g["next_token"][keep], ref["next_token"][keep]):
+        bad = np.flatnonzero(g["next_token"][keep] != ref["next_token"][keep])
+        raise AssertionError(f"next_token differs for sequences {bad}: gpu {g['next_token'][keep][bad]} "
+                             f"oracle {ref['next_token'][keep][bad]} top2 gaps {ref['top2_gap'][keep][bad]}")
+    assert np.array_equal(g["status"][keep] & ~info_bits, ref["status"][keep].astype(np.int64)), \
+        (g["status"][keep], ref["status"][keep])
+    return rep
