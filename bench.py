@@ -33,6 +33,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sets", type=int, default=N_SETS)
+    ap.add_argument("--stats-path", type=int, default=0, help="0 library default, 1 two-kernel path, 2 single-read kernel")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (sequences are independent, so the "
@@ -61,9 +62,11 @@ def main():
     out = am.binding.alloc_verify_result(B, K)
     torch.cuda.synchronize()
 
+    opts = am.Options(stats_path=args.stats_path)
+
     def step(i):
         t, d, x, seed = sets[i % len(sets)]
-        am.verify(t, d, x, ws, state=state, seed=seed, round0=i, out=out)
+        am.verify(t, d, x, ws, state=state, seed=seed, round0=i, options=opts, out=out)
         am.update_thresholds(state, K, out.n_accept, out.H_q, out.d_js)
 
     for i in range(args.warmup):
@@ -152,7 +155,8 @@ def main():
                    "step": "adasd_verify + adasd_update_thresholds"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "row_stats + jsd (statistics stage)", "algorithmic_bytes": algo_bytes,
+                     "kernel": "k_stats_fused" if "jsd" not in kern_us else "k_rowstats + k_jsd",
+                     "algorithmic_bytes": algo_bytes,
                      "kernel_us": stats_us},
         "cpu_baseline": cpu,
         "kernel_us": kern_us,

@@ -100,6 +100,12 @@ typedef struct {
   int32_t relaxed_off; /* 1: Bayesian test disabled (the "Gen-Only" ablation of Section 5.3) */
   float d_eps;         /* distances <= d_eps or >= 1-d_eps count as "exactly 0 or 1" and are not
                           recorded (Section 4.4); 0 selects the default 1e-6 */
+  int32_t stats_path;  /* kernels of the statistics stage: 0 the library's choice (the two-kernel
+                          path, the faster one on gfx950 where the stage is bound by the vector
+                          ALU); 1 the two-kernel path (normalisers, then JS distance: the logits
+                          are read twice); 2 the single-read kernel when every row is 16-byte
+                          aligned and V is a whole number of 16-byte vectors, else the two-kernel
+                          path.  Same results to the documented tolerance either way. */
 } adasd_options;
 
 /*
@@ -200,12 +206,21 @@ int adasd_update_thresholds(const adasd_state *st /* host */, int k_max, const i
  * adasd_profile_enable(n) creates n pairs of HIP events per kernel class and makes the entry points
  * record them around their kernels; adasd_profile_read waits for the recorded events and returns the
  * summed duration and launch count of one class since the last enable; adasd_profile_disable frees
- * the events.  Kernel classes: 0 row statistics (normalisers + entropy), 1 JS distance, 2 decision,
+ * the events.  Kernel classes: 0 row statistics (normalisers + entropy; the fused kernel also
+ * produces the JS distance and then class 1 stays empty), 1 JS distance (two-pass form), 2 decision,
  * 3 token sampling, 4 state update, 5 draft entropy.
  */
 int adasd_profile_enable(int max_launches);
 int adasd_profile_read(int kernel_class, double *total_ms /* host */, int *launches /* host */);
 int adasd_profile_disable(void);
+
+/*
+ * Test hook for the fused statistics kernel's bounded wait: its workgroups poll an arrival mask at
+ * most `polls` times (default 65536, roughly 15 ms) before they stop waiting and recompute the missing
+ * slices themselves, which gives bit-identical results.  0 makes every workgroup take that path at
+ * once; tests use it to exercise the path without any wave ever spinning for long.
+ */
+int adasd_set_spin_limit(int polls);
 
 const char *adasd_strerror(int code);
 int adasd_version(void);

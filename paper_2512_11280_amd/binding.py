@@ -36,7 +36,8 @@ class _State(C.Structure):
 
 class _Options(C.Structure):
     _fields_ = [("base_test", C.c_int32), ("reject_rule", C.c_int32), ("kde_min_n", C.c_int32),
-                ("bw_rule", C.c_int32), ("relaxed_off", C.c_int32), ("d_eps", C.c_float)]
+                ("bw_rule", C.c_int32), ("relaxed_off", C.c_int32), ("d_eps", C.c_float),
+                ("stats_path", C.c_int32)]
 
 
 class _VerifyArgs(C.Structure):
@@ -122,10 +123,11 @@ class Options:
     bw_rule: int = 0
     relaxed_off: int = 0
     d_eps: float = 1e-6
+    stats_path: int = 0
 
     def _c(self) -> _Options:
         return _Options(self.base_test, self.reject_rule, self.kde_min_n, self.bw_rule,
-                        self.relaxed_off, self.d_eps)
+                        self.relaxed_off, self.d_eps, self.stats_path)
 
 
 def workspace_bytes(B: int, k_max: int, V: int, dtype: torch.dtype) -> int:
@@ -273,6 +275,10 @@ def update_thresholds(state: State, k_max: int, n_accept: torch.Tensor, H_q: tor
         C.byref(st), k_max, n_accept.data_ptr(), _p(draft_len), H_q.data_ptr(), d_js.data_ptr(),
         C.byref(opt) if opt is not None else None, _p(status), _stream())
     _check(rc, "adasd_update_thresholds")
+
+
+def set_spin_limit(polls: int):
+    _check(load_library().adasd_set_spin_limit(polls), "adasd_set_spin_limit")
 
 
 def profile_enable(max_launches: int):

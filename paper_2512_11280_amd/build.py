@@ -9,12 +9,15 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libadasd.so")
-SOURCES = ["stats.hip", "decide.hip", "sample.hip", "api.hip"]
+SOURCES = ["stats.hip", "stats_fused.hip", "decide.hip", "sample.hip", "api.hip"]
 HEADERS = [os.path.join(CSRC, "device_common.h"), os.path.join(CSRC, "internal.h"),
            os.path.join(os.path.dirname(HERE), "include", "adasd.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
+         # fused multiply-adds only where the source says fmaf: the same expression must round the
+         # same way in every inlined copy (a recomputed partial result has to be bit-identical)
+         "-ffp-contract=off",
          # packed-FP32 instructions are kept out of every kernel of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -1,4 +1,5 @@
 // C ABI of libadasd: argument validation, workspace carving and kernel enqueue.
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -11,6 +12,8 @@ namespace {
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+std::atomic<int> g_spin_limit{1 << 16};
 
 // ---- optional kernel timing ----------------------------------------------------------------
 constexpr int kClasses = 6;
@@ -41,38 +44,57 @@ struct Scope {   // records a start event now and a stop event at destruction
 
 }  // namespace
 
-size_t workspace_layout(int B, int K, Workspace* ws, void* base) {
-  const size_t rows = (size_t)B * (K > 0 ? (size_t)K * 2 : 1);
-  const size_t positions = (size_t)B * (K > 0 ? K : 1);
-  size_t off = 0;
-  auto take = [&](size_t bytes) {
-    size_t at = off;
-    off = align_up(off + bytes, 256);
-    return at;
-  };
-  // Arrival counters sit at fixed offsets sized for the compiled limits, so that calls of different
-  // shapes sharing one workspace agree on where they are (they must read zero at entry).
-  const size_t o_t1 = take(65536 * sizeof(int32_t));
-  const size_t o_t2 = take(32768 * sizeof(int32_t));
-  const size_t o_t3 = take(32768 * sizeof(int32_t));
-  const size_t o_p1 = take(rows * kMaxSplit * sizeof(float4));
-  const size_t o_rows = take(rows * sizeof(RowResult));
-  const size_t o_p2 = take(positions * kMaxSplit * sizeof(float2));
-  const size_t o_plan = take((size_t)B * sizeof(SamplePlan));
-  const size_t o_p3 = take((size_t)B * kMaxSampleSplit * sizeof(Top2));
-  if (ws) {
+namespace {
+constexpr size_t kHeaderBytes = (65536 + 32768 + 32768) * sizeof(int32_t);
+// bytes per position of every shape-dependent region (per-sequence regions are sized per position too)
+constexpr size_t kRegionBytes[] = {
+    kCntStride * sizeof(int32_t),                         // fused_cnt
+    (size_t)kMaxFusedSplit * kSlotWords * sizeof(uint64_t),  // fused_slots
+    (size_t)kSlotWords * sizeof(uint64_t),                // fused_norm
+    2 * (size_t)kMaxSplit * sizeof(float4),               // part1
+    2 * sizeof(RowResult),                                // rows
+    (size_t)kMaxSplit * sizeof(float2),                   // part2
+    sizeof(SamplePlan),                                   // plan
+    (size_t)kMaxSampleSplit * sizeof(Top2),               // part3
+};
+constexpr size_t per_position_bytes() {
+  size_t t = 0;
+  for (size_t r : kRegionBytes) t += r;
+  return t;
+}
+}  // namespace
+
+size_t workspace_bytes_for(size_t positions) {
+  return kHeaderBytes + (positions + 1) * per_position_bytes() + 8 * 256;
+}
+
+size_t workspace_layout(size_t ws_bytes, Workspace* ws, void* base) {
+  const size_t slack = kHeaderBytes + 8 * 256;
+  if (ws_bytes <= slack) return 0;
+  const size_t cap = (ws_bytes - slack) / per_position_bytes();
+  if (ws && cap > 0) {
     char* p = static_cast<char*>(base);
-    ws->ticket1 = reinterpret_cast<int32_t*>(p + o_t1);
-    ws->ticket2 = reinterpret_cast<int32_t*>(p + o_t2);
-    ws->ticket3 = reinterpret_cast<int32_t*>(p + o_t3);
-    ws->part1 = reinterpret_cast<float4*>(p + o_p1);
-    ws->rows = reinterpret_cast<RowResult*>(p + o_rows);
-    ws->part2 = reinterpret_cast<float2*>(p + o_p2);
-    ws->plan = reinterpret_cast<SamplePlan*>(p + o_plan);
-    ws->part3 = reinterpret_cast<Top2*>(p + o_p3);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+      size_t at = off;
+      off = align_up(off + bytes, 256);
+      return p + at;
+    };
+    // arrival counters of the two-pass and sampling kernels: fixed size, sized for the compiled limits
+    ws->ticket1 = reinterpret_cast<int32_t*>(take(65536 * sizeof(int32_t)));
+    ws->ticket2 = reinterpret_cast<int32_t*>(take(32768 * sizeof(int32_t)));
+    ws->ticket3 = reinterpret_cast<int32_t*>(take(32768 * sizeof(int32_t)));
+    ws->fused_cnt = reinterpret_cast<int32_t*>(take(cap * kRegionBytes[0]));
+    ws->fused_slots = reinterpret_cast<uint64_t*>(take(cap * kRegionBytes[1]));
+    ws->fused_norm = reinterpret_cast<uint64_t*>(take(cap * kRegionBytes[2]));
+    ws->part1 = reinterpret_cast<float4*>(take(cap * kRegionBytes[3]));
+    ws->rows = reinterpret_cast<RowResult*>(take(cap * kRegionBytes[4]));
+    ws->part2 = reinterpret_cast<float2*>(take(cap * kRegionBytes[5]));
+    ws->plan = reinterpret_cast<SamplePlan*>(take(cap * kRegionBytes[6]));
+    ws->part3 = reinterpret_cast<Top2*>(take(cap * kRegionBytes[7]));
     ws->bytes = off;
   }
-  return off;
+  return cap;
 }
 
 }  // namespace adasd
@@ -108,8 +130,8 @@ int adasd_workspace_bytes(int B, int k_max, int V, adasd_dtype dt, size_t* bytes
   if (!bytes) return ADASD_ERR_INVALID_ARG;
   int rc = check_shape(B, k_max, V, (int)dt);
   if (rc) return rc;
-  // large enough for a verify call of this shape and for draft-entropy calls with the same B
-  *bytes = workspace_layout(B, k_max > 0 ? k_max : 1, nullptr, nullptr);
+  // large enough for a verify call of this shape and for draft-entropy calls with up to B*max(k,1) rows
+  *bytes = workspace_bytes_for((size_t)B * (size_t)(k_max > 0 ? k_max : 1));
   return ADASD_OK;
 }
 
@@ -166,7 +188,7 @@ int adasd_draft_entropy(const void* draft_logits, adasd_dtype dt, int B, int V, 
   if (!workspace) return ADASD_ERR_WORKSPACE;
   if (!aligned_to(workspace, 256)) return ADASD_ERR_MISALIGNED;
   Workspace ws;
-  if (workspace_layout(B, 0, &ws, workspace) > ws_bytes) return ADASD_ERR_WORKSPACE;
+  if (workspace_layout(ws_bytes, &ws, workspace) < (size_t)B) return ADASD_ERR_WORKSPACE;
 
   RowMap map{};
   map.base[0] = static_cast<const char*>(draft_logits);
@@ -193,6 +215,7 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   if (opt.base_test != 0) return ADASD_ERR_UNSUPPORTED;
   if (opt.reject_rule != 0 && opt.reject_rule != 1) return ADASD_ERR_INVALID_ARG;
   if (opt.bw_rule != 0 && opt.bw_rule != 1) return ADASD_ERR_INVALID_ARG;
+  if (opt.stats_path < 0 || opt.stats_path > 2) return ADASD_ERR_INVALID_ARG;
   if (a->B == 0) return ADASD_OK;
   const int B = a->B, K = a->k_max, V = a->V;
   if (!a->target_logits || !a->n_accept || !a->next_token || !a->status) return ADASD_ERR_INVALID_ARG;
@@ -215,7 +238,8 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   if (!a->workspace) return ADASD_ERR_WORKSPACE;
   if (!aligned_to(a->workspace, 256)) return ADASD_ERR_MISALIGNED;
   Workspace ws;
-  if (workspace_layout(B, K > 0 ? K : 1, &ws, a->workspace) > a->ws_bytes) return ADASD_ERR_WORKSPACE;
+  if (workspace_layout(a->ws_bytes, &ws, a->workspace) < (size_t)B * (size_t)(K > 0 ? K : 1))
+    return ADASD_ERR_WORKSPACE;
 
   hipStream_t st = (hipStream_t)stream;
   RowMap map{};
@@ -233,7 +257,11 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
 
   VerifyOut vout{a->H_p, a->H_q, a->d_js};
   DraftOut dout{nullptr, nullptr, nullptr, 0};
-  if (K > 0) {
+  int fNV = 0, fS = 0;
+  if (K > 0 && opt.stats_path == 2 && fused_plan(map, (int)a->dt, &fNV, &fS)) {
+    Scope sc(0, st);
+    if (launch_stats_fused(map, (int)a->dt, fNV, fS, g_spin_limit.load(), ws, vout, st) != hipSuccess) return ADASD_ERR_HIP;
+  } else if (K > 0) {
     const int rows = B * K * 2;
     const int S = pick_split(rows, V, (int)a->dt);
     {
@@ -320,6 +348,12 @@ int adasd_update_thresholds(const adasd_state* st, int k_max, const int32_t* n_a
   hipStream_t s = (hipStream_t)stream;
   Scope sc(4, s);
   return launch_update(u, s) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
+}
+
+int adasd_set_spin_limit(int polls) {
+  if (polls < 0) return ADASD_ERR_INVALID_ARG;
+  g_spin_limit.store(polls);
+  return ADASD_OK;
 }
 
 int adasd_profile_enable(int max_launches) {

@@ -11,6 +11,9 @@ namespace adasd {
 
 constexpr int kMaxSplit = 64;        // vocabulary slices per row (statistics kernels)
 constexpr int kMaxSampleSplit = 128; // vocabulary slices per sequence (sampling kernel)
+constexpr int kMaxFusedSplit = 128;  // wavefront slices per row pair in the fused statistics kernel
+constexpr int kSlotWords = 4;        // 64-bit words per (position, slice) of the fused kernel
+constexpr int kCntStride = 32;       // ints between the counters of two positions (one 128-byte line each)
 
 // Where the rows of one call live.  which = 0: target, 1: draft.
 struct RowMap {
@@ -31,10 +34,17 @@ struct Workspace {
   SamplePlan* plan;   // [B]
   Top2* part3;        // [B][kMaxSampleSplit]
   int32_t* ticket3;   // [B]
+  int32_t* fused_cnt; // [positions][kCntStride] arrival counters of the fused kernel, one per 128-byte line
+  uint64_t* fused_slots; // [positions][kMaxFusedSplit][kSlotWords] self-validating hand-off words, zero between calls
+  uint64_t* fused_norm;  // [positions][kSlotWords] folded triples of both rows, published by the position's leader
   size_t bytes;
 };
 
-size_t workspace_layout(int B, int K, Workspace* ws, void* base);
+// Region offsets depend only on the size of the workspace (not on the shape of the call), so calls of
+// different shapes can share one workspace: counters and hand-off words are always found where the
+// previous call left them zeroed.  Returns the number of positions the workspace can serve.
+size_t workspace_bytes_for(size_t positions);
+size_t workspace_layout(size_t ws_bytes, Workspace* ws, void* base);
 
 struct DraftOut {     // draft-entropy epilogue
   const float* T_G;
@@ -53,6 +63,9 @@ int pick_split(int rows, int V, int dt);
 
 hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Workspace& ws,
                            const VerifyOut& vout, const DraftOut& dout, hipStream_t st);
+bool fused_plan(const RowMap& map, int dt, int* NV_out, int* S_out);
+hipError_t launch_stats_fused(const RowMap& map, int dt, int NV, int S, int spin_limit,
+                              const Workspace& ws, const VerifyOut& vout, hipStream_t st);
 hipError_t launch_jsd(const RowMap& map, int dt, int S, const Workspace& ws, const VerifyOut& vout,
                       hipStream_t st);
 

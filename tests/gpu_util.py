@@ -31,8 +31,11 @@ def state_to_device(am, host_state, B, cap):
     return st
 
 
-def run_gpu(am, batch, options=None, seq_id=None, rounds=None, ws=None):
+def run_gpu(am, batch, options=None, seq_id=None, rounds=None, ws=None, stats_path=0):
     B, K, V = batch.B, batch.k, batch.V
+    if stats_path:
+        import dataclasses
+        options = dataclasses.replace(options or am.Options(), stats_path=stats_path)
     ws = ws or am.Workspace(B, max(K, 1), V, batch.target.dtype)
     cap = batch.state["LA"].shape[1]
     st = state_to_device(am, batch.state, B, cap)
@@ -51,10 +54,17 @@ def run_oracle(oracle, batch, options=None, seq_id=None, rounds=None):
         kw = dict(reject_rule=options.reject_rule, kde_min_n=options.kde_min_n,
                   bw_rule=options.bw_rule, relaxed_off=options.relaxed_off)
     s = batch.state
-    return oracle.verify(batch.target, batch.draft, batch.draft_tokens.numpy(),
-                         draft_len=None if batch.draft_len is None else batch.draft_len.numpy(),
-                         LA=s["LA"], LR=s["LR"], nA=s["nA"], nR=s["nR"], seed=batch.seed,
-                         seq_id=seq_id, rounds=rounds, round0=batch.round0, **kw)
+    ref = oracle.verify(batch.target, batch.draft, batch.draft_tokens.numpy(),
+                        draft_len=None if batch.draft_len is None else batch.draft_len.numpy(),
+                        LA=s["LA"], LR=s["LR"], nA=s["nA"], nR=s["nR"], seed=batch.seed,
+                        seq_id=seq_id, rounds=rounds, round0=batch.round0, **kw)
+
+    def posterior_at(b, d):
+        """The oracle's posterior of sequence b at a given distance (for the p_accept check)."""
+        return oracle.posterior(float(d), s["LA"][b, :int(s["nA"][b])], s["LR"][b, :int(s["nR"][b])],
+                                min_n=kw.get("kde_min_n", 2), bw_rule=kw.get("bw_rule", 0))
+    ref["posterior_at"] = posterior_at
+    return ref
 
 
 def close(gpu, ref, rtol=RTOL, atol=ATOL):
@@ -78,8 +88,15 @@ def compare_verify(gpu, ref, info_bits=16):
             bad = np.argwhere(~ok)[0]
             raise AssertionError(f"{name} mismatch at {tuple(bad)}: gpu {g[name][tuple(bad)]!r} "
                                  f"oracle {ref[name][tuple(bad)]!r}")
+    # The posterior is a steep function of the distance where the kernel bandwidth is small, so an
+    # admissible error of the distance can move it by more than PA_ATOL.  Where the direct comparison
+    # fails, the posterior must still agree with the oracle's evaluated at the distance the GPU found.
     okp = close(g["p_accept"], ref["p_accept"], rtol=0.0, atol=PA_ATOL)
-    assert okp.all(), f"p_accept mismatch: max diff {np.nanmax(np.abs(g['p_accept'] - ref['p_accept']))}"
+    for b, i in np.argwhere(~okp):
+        at_gpu_d = ref["posterior_at"](b, g["d_js"][b, i])
+        assert abs(g["p_accept"][b, i] - at_gpu_d) <= PA_ATOL, \
+            f"p_accept mismatch at {(b, i)}: gpu {g['p_accept'][b, i]!r}, oracle at the same distance " \
+            f"{at_gpu_d!r}, oracle at its own distance {ref['p_accept'][b, i]!r}"
     rep["max_rel_H"] = float(np.nanmax(np.abs(g["H_q"] - ref["H_q"]) / np.maximum(np.abs(ref["H_q"]), 1e-30),
                                        initial=0.0))
     rep["max_rel_d"] = float(np.nanmax(np.abs(g["d_js"] - ref["d_js"]) / np.maximum(np.abs(ref["d_js"]), 1e-30),

@@ -24,6 +24,12 @@ def wl():
     return workloads
 
 
+@pytest.fixture(params=[2, 1], ids=["singleread", "twokernel"])
+def path(request):
+    """Both implementations of the statistics stage must meet the same bar."""
+    return request.param
+
+
 def _report(name, rep):
     print(f"[parity] {name}: flips={rep['flips']} skipped_seq={rep['seq_skipped']} "
           f"exact_path={rep['exact_path']} max_rel_H={rep['max_rel_H']:.2e} max_rel_d={rep['max_rel_d']:.2e}",
@@ -31,19 +37,19 @@ def _report(name, rep):
 
 
 # ------------------------------------------------------------------------------- the five shapes
-def test_config_tiny_fp32(am, wl, oracle):
+def test_config_tiny_fp32(am, wl, oracle, path):
     batch = wl.config_tiny()
-    out, _, _ = G.run_gpu(am, batch)
+    out, _, _ = G.run_gpu(am, batch, stats_path=path)
     rep = G.compare_verify(out, G.run_oracle(oracle, batch))
     _report("tiny", rep)
     assert rep["flips"] == 0
 
 
 @pytest.mark.parametrize("with_state", [True, False])
-def test_config_single_stream_bf16(am, wl, oracle, with_state):
+def test_config_single_stream_bf16(am, wl, oracle, with_state, path):
     batch = wl.config_single_stream(with_state=with_state)
     ws = am.Workspace(8, 8, batch.V, torch.bfloat16)      # also serves the 8-row draft-entropy call
-    out, _, _ = G.run_gpu(am, batch, ws=ws)
+    out, _, _ = G.run_gpu(am, batch, stats_path=path, ws=ws)
     ref = G.run_oracle(oracle, batch)
     rep = G.compare_verify(out, ref)
     _report(f"single_stream(state={with_state})", rep)
@@ -60,10 +66,10 @@ def test_config_single_stream_bf16(am, wl, oracle, with_state):
     assert stop_ref.min() == 0 and stop_ref.max() == 1
 
 
-def test_config_batched_reduced(am, wl, oracle):
+def test_config_batched_reduced(am, wl, oracle, path):
     # same generator and vocabulary as the headline shape, fewer sequences so the oracle takes seconds
     batch = wl.config_batched(B=8, k=8)
-    out, _, _ = G.run_gpu(am, batch)
+    out, _, _ = G.run_gpu(am, batch, stats_path=path)
     ref = G.run_oracle(oracle, batch)
     rep = G.compare_verify(out, ref)
     _report("batched(B=8)", rep)
@@ -71,20 +77,20 @@ def test_config_batched_reduced(am, wl, oracle):
     assert (ref["accept_mask"] == 2).any()      # the Bayesian test decides some positions
 
 
-def test_config_large_reduced(am, wl, oracle):
+def test_config_large_reduced(am, wl, oracle, path):
     batch = wl.config_large(B=6, k=16)
-    out, _, _ = G.run_gpu(am, batch)
+    out, _, _ = G.run_gpu(am, batch, stats_path=path)
     ref = G.run_oracle(oracle, batch)
     rep = G.compare_verify(out, ref)
     _report("large(B=6,k=16,V=152064)", rep)
 
 
-def test_ragged_lengths_sequence_ids_and_rounds(am, wl, oracle):
+def test_ragged_lengths_sequence_ids_and_rounds(am, wl, oracle, path):
     batch = wl.config_batched(B=6, k=5, V=32003, seed=99)       # V not a multiple of 8: scalar tail
     batch.draft_len = torch.tensor([0, 1, 5, 3, 2, 5], dtype=torch.int32)
     seq_id = [7, 1 << 31, 3, 3, 0xFFFFFFFF, 12]
     rounds = [0, 5, 1000, 1001, 2, 3]
-    out, _, _ = G.run_gpu(am, batch, seq_id=seq_id, rounds=rounds)
+    out, _, _ = G.run_gpu(am, batch, stats_path=path, seq_id=seq_id, rounds=rounds)
     ref = G.run_oracle(oracle, batch, seq_id=seq_id, rounds=rounds)
     rep = G.compare_verify(out, ref)
     _report("ragged", rep)
@@ -93,9 +99,9 @@ def test_ragged_lengths_sequence_ids_and_rounds(am, wl, oracle):
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("V", [8, 100, 1001, 4096, 20011])
-def test_small_and_ragged_vocabularies(am, wl, oracle, dtype, V):
+def test_small_and_ragged_vocabularies(am, wl, oracle, dtype, V, path):
     batch = wl.config_batched(B=5, k=3, V=V, dtype=dtype, seed=V)
-    out, _, _ = G.run_gpu(am, batch)
+    out, _, _ = G.run_gpu(am, batch, stats_path=path)
     rep = G.compare_verify(out, G.run_oracle(oracle, batch))
     _report(f"V={V},{dtype}", rep)
 
@@ -116,7 +122,7 @@ def test_unaligned_rows_take_the_elementwise_path(am, wl, oracle):
     _report("unaligned", rep)
 
 
-def test_nearly_identical_distributions(am, wl, oracle):
+def test_nearly_identical_distributions(am, wl, oracle, path):
     """Small JS distances: flat rows with a slightly perturbed draft, and peaked rows where both
     models put ~0.999 on one token (the regime the paper reports as distances 'equal to 0')."""
     V, K = 128256, 6
@@ -131,7 +137,7 @@ def test_nearly_identical_distributions(am, wl, oracle):
         d[0, i, 1000 + i] = zd
     tok = torch.full((1, K), 1003, dtype=torch.int32)
     batch = wl.VerifyBatch(t.to(torch.bfloat16), d.to(torch.bfloat16), tok, None, wl.empty_state(1, 8), 3)
-    out, _, _ = G.run_gpu(am, batch)
+    out, _, _ = G.run_gpu(am, batch, stats_path=path)
     ref = G.run_oracle(oracle, batch)
     print("[small d] oracle d:", ref["d_js"][0], "gpu d:", out.d_js[0].cpu().numpy(), flush=True)
     rep = G.compare_verify(out, ref)
@@ -157,7 +163,7 @@ def test_option_variants(am, wl, oracle, opt):
 
 
 # ------------------------------------------------------------------------------- degenerate inputs
-def test_masked_identical_and_disjoint_rows(am, wl, oracle):
+def test_masked_identical_and_disjoint_rows(am, wl, oracle, path):
     V, K = 4100, 4
     g = torch.Generator().manual_seed(3)
     t = torch.randn(1, K + 1, V, generator=g) * 3
@@ -169,7 +175,7 @@ def test_masked_identical_and_disjoint_rows(am, wl, oracle):
     d[0, 3, 17] = ninf
     tok = torch.tensor([[3, V // 2 - 1, 7, 17]], dtype=torch.int32)   # q(x)>0,p(x)=0 | p=0 | q(x)=0
     batch = wl.VerifyBatch(t.to(torch.bfloat16), d.to(torch.bfloat16), tok, None, wl.empty_state(1, 8), 5)
-    out, _, _ = G.run_gpu(am, batch)
+    out, _, _ = G.run_gpu(am, batch, stats_path=path)
     ref = G.run_oracle(oracle, batch)
     rep = G.compare_verify(out, ref)
     _report("masked", rep)
@@ -178,7 +184,7 @@ def test_masked_identical_and_disjoint_rows(am, wl, oracle):
     assert ref["n_accept"][0] == 1
 
 
-def test_status_bits_and_exact_path(am, wl, oracle):
+def test_status_bits_and_exact_path(am, wl, oracle, path):
     V = 2048
     g = torch.Generator().manual_seed(4)
     z = (torch.randn(V, generator=g) * 2).to(torch.bfloat16)
@@ -190,7 +196,7 @@ def test_status_bits_and_exact_path(am, wl, oracle):
     t[3, 1, 7] = float("inf")            # +inf in the bonus row only
     t[4, 1, :] = float("-inf")           # bonus row without any finite logit
     batch = wl.VerifyBatch(t, d, tok, None, wl.empty_state(B, 8), 11)
-    out, _, _ = G.run_gpu(am, batch)
+    out, _, _ = G.run_gpu(am, batch, stats_path=path)
     ref = G.run_oracle(oracle, batch)
     rep = G.compare_verify(out, ref)
     _report("status", rep)
@@ -368,11 +374,29 @@ def test_closed_loop_rounds_against_oracle(am, wl, oracle):
     assert lens.max() > 1                # the threshold has adapted upwards since
 
 
-def test_results_are_bitwise_reproducible(am, wl):
+def test_bounded_wait_expiry_gives_identical_results(am, wl):
+    """With a spin limit of 0 every workgroup of the single-read kernel stops waiting at once and
+    recomputes the other slices' results itself; the outputs must not change by a single bit."""
+    batch = wl.config_batched(B=4, k=4, V=128256, seed=321)
+    a, _, ws = G.run_gpu(am, batch, stats_path=2)
+    snap = {k: getattr(a, k).clone() for k in ("n_accept", "next_token", "H_p", "H_q", "d_js", "p_accept")}
+    am.set_spin_limit(0)
+    try:
+        b, _, _ = G.run_gpu(am, batch, ws=ws, stats_path=2)
+    finally:
+        am.set_spin_limit(1 << 16)
+    for k, v in snap.items():
+        assert torch.equal(getattr(b, k), v, ), k
+    c, _, _ = G.run_gpu(am, batch, ws=ws, stats_path=2)   # and the workspace is clean afterwards
+    for k, v in snap.items():
+        assert torch.equal(getattr(c, k), v), k
+
+
+def test_results_are_bitwise_reproducible(am, wl, path):
     batch = wl.config_batched(B=4, k=4, V=50000, seed=123)
-    a, _, ws = G.run_gpu(am, batch)
+    a, _, ws = G.run_gpu(am, batch, stats_path=path)
     snap = {k: getattr(a, k).clone() for k in ("n_accept", "next_token", "H_p", "H_q", "d_js", "p_accept")}
     for _ in range(3):
-        b, _, _ = G.run_gpu(am, batch, ws=ws)
+        b, _, _ = G.run_gpu(am, batch, ws=ws, stats_path=path)
         for k, v in snap.items():
             assert torch.equal(getattr(b, k), v), k
