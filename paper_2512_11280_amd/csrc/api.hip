@@ -3,6 +3,8 @@
 #include <mutex>
 #include <vector>
 
+#include <cstdlib>
+
 #include "internal.h"
 
 namespace adasd {
@@ -316,7 +318,11 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   s.round0 = a->round0;
   s.next_token = a->next_token;
   s.status = a->status;
-  int S3 = pick_split(B * 8, V, (int)a->dt);
+  // about two 16-byte vectors per thread: enough workgroups to cover the chip for a handful of rows
+  const int nvec = V / ((int)a->dt == ADASD_BF16 ? 8 : 4);
+  int S3 = (nvec + 2 * kBlock - 1) / (2 * kBlock);
+  if (const char* e = getenv("ADASD_SPLIT3")) S3 = atoi(e);   // tuning experiments only
+  if (S3 < 1) S3 = 1;
   if (S3 > kMaxSampleSplit) S3 = kMaxSampleSplit;
   {
     Scope sc(3, st);

@@ -13,6 +13,19 @@ constexpr float kLog2e = 1.44269504088896340736f;
 constexpr double kLn2 = 0.693147180559945309417232;
 constexpr float kNegHuge = -3.0e38f;        // finite stand-in for "no element seen yet"
 
+// Kernel arguments are fetched with scalar loads where they are first needed, one 64-byte line at a
+// time, and right after a launch every line misses all the way to memory: a kernel with a few
+// hundred bytes of arguments pays that latency several times in a row before it issues its first
+// load of data.  Touching every line at the very top makes those misses overlap.
+template <int BYTES> __device__ __forceinline__ void warm_kernargs() {
+  const __attribute__((address_space(4))) int* ka =
+      (const __attribute__((address_space(4))) int*)__builtin_amdgcn_kernarg_segment_ptr();
+  int t = 0;
+#pragma unroll
+  for (int off = 0; off < BYTES; off += 64) t ^= ka[off / 4];
+  asm volatile("" ::"s"(t));
+}
+
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }  // v_exp_f32
 __device__ __forceinline__ float lg2(float x) { return __builtin_amdgcn_logf(x); }   // v_log_f32
 
@@ -113,6 +126,91 @@ __device__ __forceinline__ double wave_max(double v) {
   for (int off = 32; off > 0; off >>= 1) v = fmax(v, __shfl_xor(v, off));
   return v;
 }
+
+// Wavefront reductions on the data-parallel-primitive path: rotations inside each row of 16 lanes
+// leave every lane with its row's result, the four row results are then combined through scalar
+// registers.  Far shorter dependent chains than six LDS permutes.
+template <int CTRL> __device__ __forceinline__ float dpp_rot(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float lane_value(float v, int lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+__device__ __forceinline__ float wave_sum_f(float v) {
+  v += dpp_rot<0x121>(v);    // row_ror:1
+  v += dpp_rot<0x122>(v);    // row_ror:2
+  v += dpp_rot<0x124>(v);    // row_ror:4
+  v += dpp_rot<0x128>(v);    // row_ror:8
+  return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
+}
+__device__ __forceinline__ float wave_max_f(float v) {
+  v = fmaxf(v, dpp_rot<0x121>(v));
+  v = fmaxf(v, dpp_rot<0x122>(v));
+  v = fmaxf(v, dpp_rot<0x124>(v));
+  v = fmaxf(v, dpp_rot<0x128>(v));
+  return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
+}
+
+__device__ __forceinline__ uint32_t pk_max_f16(uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
+template <int DT> __device__ __forceinline__ uint4 neutral_vec() {   // all logits -inf
+  return DT == ADASD_BF16 ? make_uint4(0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u)
+                          : make_uint4(0xFF800000u, 0xFF800000u, 0xFF800000u, 0xFF800000u);
+}
+
+// Largest finite logit held in NV vectors, times log2(e) (kNegHuge if there is none).
+// bf16 pairs are compared as packed f16: both formats order their bit patterns the same way, and
+// the bf16 patterns of +-inf / NaN read as f16 NaNs, which the packed max ignores.
+template <int DT, int NV> __device__ __forceinline__ float vecs_max(const uint4 (&v)[NV]) {
+  if (DT == ADASD_BF16) {
+    uint32_t m = pk_max_f16(v[0].x, v[0].y);
+    m = pk_max_f16(m, v[0].z);
+    m = pk_max_f16(m, v[0].w);
+#pragma unroll
+    for (int j = 1; j < NV; ++j) {
+      m = pk_max_f16(m, v[j].x);
+      m = pk_max_f16(m, v[j].y);
+      m = pk_max_f16(m, v[j].z);
+      m = pk_max_f16(m, v[j].w);
+    }
+    // a half whose f16 exponent field is all ones was never a finite logit of sane size
+    uint32_t lo = m << 16, hi = m & 0xffff0000u;
+    float flo = ((m & 0x7C00u) == 0x7C00u) ? kNegHuge : __uint_as_float(lo) * kLog2e;
+    float fhi = ((m & 0x7C000000u) == 0x7C000000u) ? kNegHuge : __uint_as_float(hi) * kLog2e;
+    return fmaxf(flo, fhi);
+  } else {
+    float m = kNegHuge;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      float a = __uint_as_float(v[j].x), b = __uint_as_float(v[j].y);
+      float c = __uint_as_float(v[j].z), d = __uint_as_float(v[j].w);
+      m = fmaxf(m, fmaxf(fmaxf(a, b), fmaxf(c, d)));   // NaN-ignoring; +inf surfaces in the sums
+    }
+    return (m > kNegHuge && m < INFINITY) ? m * kLog2e : kNegHuge;
+  }
+}
+
+// Phase-1 accumulation of one vector into per-lane sums relative to the reference m.
+template <int DT>
+__device__ __forceinline__ void lse_accum(const uint4& v, float m, float& s0, float& s1, float& u0, float& u1) {
+  constexpr int EPV = Elem<DT>::per_vec;
+  float z[EPV];
+  unpack<DT>(v, z);
+#pragma unroll
+  for (int e = 0; e < EPV; e += 2) {
+    float t0 = fmaf(z[e], kLog2e, -m), t1 = fmaf(z[e + 1], kLog2e, -m);
+    float e0 = ex2(t0), e1 = ex2(t1);
+    s0 += e0;
+    s1 += e1;
+    u0 = fmaf(fmaxf(t0, -200.f), e0, u0);   // masked logits: (-200) * 0 = 0; a NaN stays one through e
+    u1 = fmaf(fmaxf(t1, -200.f), e1, u1);
+  }
+}
+
 
 // Cross-workgroup hand-off without a cache write-back.  An agent-scope fence on gfx950 writes back
 // and invalidates the XCD's whole L2, which serialises badly when every workgroup does it.  Instead

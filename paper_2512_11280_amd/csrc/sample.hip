@@ -14,42 +14,63 @@ namespace {
 constexpr float kErrRel = 1.52587890625e-05f;   // 2^-16: bound on the relative error of a float p or q
 constexpr float kGuard = 1.220703125e-04f;      // 2^-13: bound on the log2-domain rounding of two keys
 
+// Word (i & 3) of a Philox block by selects: indexing the array with a run-time value would make the
+// compiler move it to LDS, and that lowering reads the dispatch packet for the workgroup size.
+__device__ __forceinline__ uint32_t pick_word(const U4& r, int i) {
+  const uint32_t lo = (i & 1) ? r.w[1] : r.w[0], hi = (i & 1) ? r.w[3] : r.w[2];
+  return (i & 2) ? hi : lo;
+}
+
 __device__ __forceinline__ bool better(float ka, int ia, float kb, int ib) {
   return ka > kb || (ka == kb && (unsigned)ia < (unsigned)ib);
 }
 
+// Running winner (key, index) and the runner-up's KEY (its index is never needed).  One lane sees its
+// elements in increasing index order, so a strict comparison keeps the lowest index on equal keys;
+// across lanes `better` decides.  No branches.
 __device__ __forceinline__ void top2_push(Top2& t, float k, int i) {
-  if (better(k, i, t.k1, t.i1)) {
-    t.k2 = t.k1; t.i2 = t.i1;
-    t.k1 = k; t.i1 = i;
-  } else if (better(k, i, t.k2, t.i2)) {
-    t.k2 = k; t.i2 = i;
-  }
+  const bool gt = k > t.k1;
+  t.k2 = fmaxf(t.k2, gt ? t.k1 : k);
+  t.i1 = gt ? i : t.i1;
+  t.k1 = gt ? k : t.k1;
 }
 
 __device__ __forceinline__ Top2 top2_merge(const Top2& a, const Top2& b) {
+  const bool aw = better(a.k1, a.i1, b.k1, b.i1);
   Top2 r;
-  if (better(a.k1, a.i1, b.k1, b.i1)) {
-    r.k1 = a.k1; r.i1 = a.i1;
-    if (better(a.k2, a.i2, b.k1, b.i1)) { r.k2 = a.k2; r.i2 = a.i2; }
-    else { r.k2 = b.k1; r.i2 = b.i1; }
-  } else {
-    r.k1 = b.k1; r.i1 = b.i1;
-    if (better(b.k2, b.i2, a.k1, a.i1)) { r.k2 = b.k2; r.i2 = b.i2; }
-    else { r.k2 = a.k1; r.i2 = a.i1; }
-  }
+  r.k2 = fmaxf(fmaxf(a.k2, b.k2), aw ? b.k1 : a.k1);
+  r.k1 = aw ? a.k1 : b.k1;
+  r.i1 = aw ? a.i1 : b.i1;
+  r.i2 = -1;
   return r;
 }
 
+template <int CTRL> __device__ __forceinline__ int dpp_rot_i(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
+}
+template <int CTRL> __device__ __forceinline__ Top2 top2_rot(const Top2& v) {
+  Top2 o;
+  o.k1 = dpp_rot<CTRL>(v.k1);
+  o.i1 = dpp_rot_i<CTRL>(v.i1);
+  o.k2 = dpp_rot<CTRL>(v.k2);
+  o.i2 = -1;
+  return o;
+}
+__device__ __forceinline__ Top2 top2_lane(const Top2& v, int lane) {
+  Top2 o;
+  o.k1 = lane_value(v.k1, lane);
+  o.i1 = __builtin_amdgcn_readlane(v.i1, lane);
+  o.k2 = lane_value(v.k2, lane);
+  o.i2 = -1;
+  return o;
+}
+// Wave-uniform result: rotations inside the rows of 16 lanes, then the four rows through scalars.
 __device__ __forceinline__ Top2 top2_wave_reduce(Top2 v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    Top2 o;
-    o.k1 = __shfl_xor(v.k1, off); o.i1 = __shfl_xor(v.i1, off);
-    o.k2 = __shfl_xor(v.k2, off); o.i2 = __shfl_xor(v.i2, off);
-    v = top2_merge(v, o);
-  }
-  return v;
+  v = top2_merge(v, top2_rot<0x121>(v));
+  v = top2_merge(v, top2_rot<0x122>(v));
+  v = top2_merge(v, top2_rot<0x124>(v));
+  v = top2_merge(v, top2_rot<0x128>(v));
+  return top2_merge(top2_merge(top2_lane(v, 0), top2_lane(v, 16)), top2_merge(top2_lane(v, 32), top2_lane(v, 48)));
 }
 
 // log2 of E = -ln(u), u = (word + 0.5) / 2^32, accurate to a few 1e-6 relative in E everywhere:
@@ -83,23 +104,36 @@ __device__ __forceinline__ void scan_slice(const char* prow, const char* qrow, i
                     (!RESIDUAL || (reinterpret_cast<uintptr_t>(qrow) & 15u) == 0);
   const int nv = fast ? V / EPV : 0;
   if (fast) {
-    const int v0 = (int)(((int64_t)s * nv) / S), v1 = (int)(((int64_t)(s + 1) * nv) / S);
+    const int chunk = (nv + S - 1) / S, v0 = min(s * chunk, nv), v1 = min(v0 + chunk, nv);
     const uint4* vp = reinterpret_cast<const uint4*>(prow);
     const uint4* vq = reinterpret_cast<const uint4*>(qrow);
-    for (int j = v0 + tid; j < v1; j += kBlock) {
-      float zp[EPV], zq[EPV];
-      unpack<DT>(vp[j], zp);
-      if (RESIDUAL) unpack<DT>(vq[j], zq);
-      const int base = j * EPV;
+    constexpr int NB = 2;                       // vectors per thread and batch, all loads in flight at once
+    for (int base_v = v0; base_v < v1; base_v += NB * kBlock) {
+      uint4 xp[NB], xq[NB];
 #pragma unroll
-      for (int g = 0; g < EPV / 4; ++g) {
-        const U4 r = philox4x32_10((uint32_t)(base >> 2) + g, c1, c2, c3, k0, k1);
+      for (int j = 0; j < NB; ++j) {
+        const int idx = min(base_v + tid + j * kBlock, v1 - 1);
+        xp[j] = vp[idx];
+        if (RESIDUAL) xq[j] = vq[idx];
+      }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float a = zp[4 * g + e];
-          if (!RESIDUAL) poison |= !(a < INFINITY);   // NaN or +inf in the bonus row
-          float k = key_ub<RESIDUAL>(a, RESIDUAL ? zq[4 * g + e] : 0.f, cp, cq, r.w[e]);
-          top2_push(best, k, base + 4 * g + e);
+      for (int j = 0; j < NB; ++j) {
+        const int idx = base_v + tid + j * kBlock;
+        const bool in = idx < v1;
+        float zp[EPV], zq[EPV];
+        unpack<DT>(xp[j], zp);
+        if (RESIDUAL) unpack<DT>(xq[j], zq);
+        const int base = idx * EPV;
+#pragma unroll
+        for (int g = 0; g < EPV / 4; ++g) {
+          const U4 r = philox4x32_10((uint32_t)(base >> 2) + g, c1, c2, c3, k0, k1);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float a = zp[4 * g + e];
+            if (!RESIDUAL) poison |= in && !(a < INFINITY);   // NaN or +inf in the bonus row
+            float k = key_ub<RESIDUAL>(a, RESIDUAL ? zq[4 * g + e] : 0.f, cp, cq, r.w[e]);
+            top2_push(best, in ? k : -INFINITY, base + 4 * g + e);
+          }
         }
       }
     }
@@ -117,7 +151,7 @@ __device__ __forceinline__ void scan_slice(const char* prow, const char* qrow, i
     const U4 r = philox4x32_10((uint32_t)v >> 2, c1, c2, c3, k0, k1);
     const float a = load_elem<DT>(prow, v);
     if (!RESIDUAL) poison |= !(a < INFINITY);
-    float k = key_ub<RESIDUAL>(a, RESIDUAL ? load_elem<DT>(qrow, v) : 0.f, cp, cq, r.w[v & 3]);
+    float k = key_ub<RESIDUAL>(a, RESIDUAL ? load_elem<DT>(qrow, v) : 0.f, cp, cq, pick_word(r, v));
     top2_push(best, k, v);
   }
 }
@@ -187,7 +221,7 @@ __device__ int sample_exact(const char* prow, const char* qrow, bool residual, i
     if (residual) w -= exp((double)load_elem<DT>(qrow, v) - lse_q);
     if (!(w > 0.0)) continue;
     const U4 r = philox4x32_10((uint32_t)v >> 2, c1, c2, c3, k0, k1);
-    const double u = ((double)r.w[v & 3] + 0.5) * (1.0 / 4294967296.0);
+    const double u = ((double)pick_word(r, v) + 0.5) * (1.0 / 4294967296.0);
     const double key = log(w) - log(-log(u));
     if (key > best) {               // v increases per thread: the first index keeps a tie
       best = key;
@@ -211,6 +245,7 @@ __device__ int sample_exact(const char* prow, const char* qrow, bool residual, i
 
 template <int DT>
 __global__ void __launch_bounds__(kBlock) k_sample(SampleArgs a, int S, Workspace ws) {
+  warm_kernargs<sizeof(SampleArgs) + sizeof(int) + sizeof(Workspace)>();
   const int b = blockIdx.y, s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const SamplePlan plan = ws.plan[b];
   if (!plan.valid) {
@@ -253,7 +288,7 @@ __global__ void __launch_bounds__(kBlock) k_sample(SampleArgs a, int S, Workspac
       t = top2_merge(t, sh_top[w]);
       flag |= sh_flag[w];
     }
-    if (flag) t.i2 = -2;   // poison marker travels in the runner-up index
+    t.i2 = flag ? -2 : -1;   // poison marker travels in the runner-up index
     Top2* dst = &ws.part3[(size_t)b * kMaxSampleSplit + s];
     st_agent(&dst->k1, t.k1); st_agent(&dst->i1, t.i1);
     st_agent(&dst->k2, t.k2); st_agent(&dst->i2, t.i2);

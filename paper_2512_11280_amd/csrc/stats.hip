@@ -4,6 +4,8 @@
 // Two-kernel split-vocabulary form: each row is cut into S slices, one workgroup per slice;
 // partial results meet in the workspace and the workgroup that arrives last at a row's counter
 // folds them (fixed butterfly order, so results do not depend on arrival order).
+#include <cstdlib>
+
 #include "internal.h"
 
 namespace adasd {
@@ -64,9 +66,10 @@ __device__ __forceinline__ void lse_push_vec(Lse& st, const uint4& q) {
 // ---------------------------------------------------------------------------------------------
 // Pass 1: partial (m, s, u) of one slice of one row; last arrival finalises lse and entropy.
 // ---------------------------------------------------------------------------------------------
-template <int DT>
+template <int DT, int kRowBatch>   // kRowBatch: vectors per thread and batch
 __global__ void __launch_bounds__(kBlock)
 k_rowstats(RowMap map, int S, Workspace ws, VerifyOut vout, DraftOut dout) {
+  warm_kernargs<sizeof(RowMap) + sizeof(int) + sizeof(Workspace) + sizeof(VerifyOut) + sizeof(DraftOut)>();
   constexpr int EPV = Elem<DT>::per_vec;
   const int rho = blockIdx.y, s = blockIdx.x, tid = threadIdx.x;
   const RowRef r = locate_row<DT>(map, rho);
@@ -78,22 +81,55 @@ k_rowstats(RowMap map, int S, Workspace ws, VerifyOut vout, DraftOut dout) {
     return;
   }
   const int V = map.V;
-  Lse st = lse_empty();
+  // Vector path: batches of kRowBatch vectors per thread are loaded up front (all loads of a batch in
+  // flight at once), the batch's largest finite logit becomes the wavefront's reference if it exceeds
+  // the current one, and every element then costs one exp and a handful of multiply-adds: no
+  // per-element rescaling, no divergent branch.  Elements outside whole vectors (unaligned rows, the
+  // last V mod EPV logits) take the one-at-a-time online form in `extra`.
+  float M = kNegHuge, s0 = 0.f, s1 = 0.f, u0 = 0.f, u1 = 0.f;
+  Lse extra = lse_empty();
   if (aligned16(r.ptr)) {
     const int nv = V / EPV;
-    const int v0 = (int)(((int64_t)s * nv) / S), v1 = (int)(((int64_t)(s + 1) * nv) / S);
+    const int chunk = (nv + S - 1) / S, v0 = min(s * chunk, nv), v1 = min(v0 + chunk, nv);
     const uint4* vec = reinterpret_cast<const uint4*>(r.ptr);
-    for (int j = v0 + tid; j < v1; j += kBlock) lse_push_vec<DT>(st, vec[j]);
+    const uint4 neutral = neutral_vec<DT>();
+    for (int base = v0; base < v1; base += kRowBatch * kBlock) {
+      uint4 v[kRowBatch];
+#pragma unroll
+      for (int j = 0; j < kRowBatch; ++j) {
+        const int idx = base + tid + j * kBlock;
+        const bool in = idx < v1;
+        const uint4 x = vec[in ? idx : v1 - 1];
+        v[j] = make_uint4(in ? x.x : neutral.x, in ? x.y : neutral.y, in ? x.z : neutral.z, in ? x.w : neutral.w);
+      }
+      const float mb = wave_max_f(vecs_max<DT, kRowBatch>(v));
+      if (mb > M) {                       // wave-uniform
+        const float d = M - mb, f = ex2(d);
+        u0 = (u0 + d * s0) * f;
+        u1 = (u1 + d * s1) * f;
+        s0 *= f;
+        s1 *= f;
+        M = mb;
+      }
+#pragma unroll
+      for (int j = 0; j < kRowBatch; ++j) lse_accum<DT>(v[j], M, s0, s1, u0, u1);
+    }
     if (s == S - 1 && tid == 0)
-      for (int v = nv * EPV; v < V; ++v) lse_push(st, load_elem<DT>(r.ptr, v));
+      for (int v = nv * EPV; v < V; ++v) lse_push(extra, load_elem<DT>(r.ptr, v));
   } else {
     const int e0 = (int)(((int64_t)s * V) / S), e1 = (int)(((int64_t)(s + 1) * V) / S);
-    for (int v = e0 + tid; v < e1; v += kBlock) lse_push(st, load_elem<DT>(r.ptr, v));
+    for (int v = e0 + tid; v < e1; v += kBlock) lse_push(extra, load_elem<DT>(r.ptr, v));
+  }
+  // wavefront fold: common reference, then plain sums
+  Lse st = lse_merge(Lse{M, s0 + s1, u0 + u1}, extra);
+  {
+    const float Mw = wave_max_f(st.m), d = st.m - Mw, f = ex2(d);
+    const float sw = wave_sum_f(st.s * f), uw = wave_sum_f((st.u + d * st.s) * f);
+    st = Lse{Mw, sw, uw};
   }
 
   __shared__ Lse sh[kWaves];
   __shared__ int sh_last;
-  st = wave_reduce(st);
   const int lane = tid & 63, wave = tid >> 6;
   if (lane == 0) sh[wave] = st;
   __syncthreads();
@@ -167,9 +203,10 @@ __device__ __forceinline__ void jsd_push(float zp, float zq, float cp, float cq,
   acc = fmaf(b, t, acc);
 }
 
-template <int DT>
+template <int DT, int kJsdBatch>   // kJsdBatch: vector pairs per thread and batch
 __global__ void __launch_bounds__(kBlock)
 k_jsd(RowMap map, int S, Workspace ws, VerifyOut vout) {
+  warm_kernargs<sizeof(RowMap) + sizeof(int) + sizeof(Workspace) + sizeof(VerifyOut)>();
   constexpr int EPV = Elem<DT>::per_vec;
   const int pos = blockIdx.y, s = blockIdx.x, tid = threadIdx.x;
   const RowRef rp = locate_row<DT>(map, 2 * pos), rq = locate_row<DT>(map, 2 * pos + 1);
@@ -185,16 +222,34 @@ k_jsd(RowMap map, int S, Workspace ws, VerifyOut vout) {
   float acc = 0.f;
   if (aligned16(rp.ptr) && aligned16(rq.ptr)) {
     const int nv = V / EPV;
-    const int v0 = (int)(((int64_t)s * nv) / S), v1 = (int)(((int64_t)(s + 1) * nv) / S);
+    const int chunk = (nv + S - 1) / S, v0 = min(s * chunk, nv), v1 = min(v0 + chunk, nv);
     const uint4* vp = reinterpret_cast<const uint4*>(rp.ptr);
     const uint4* vq = reinterpret_cast<const uint4*>(rq.ptr);
-    for (int j = v0 + tid; j < v1; j += kBlock) {
-      float zp[EPV], zq[EPV];
-      unpack<DT>(vp[j], zp);
-      unpack<DT>(vq[j], zq);
+    const uint4 neutral = neutral_vec<DT>();
+    float acc1 = 0.f;
+    for (int base = v0; base < v1; base += kJsdBatch * kBlock) {
+      uint4 xp[kJsdBatch], xq[kJsdBatch];
 #pragma unroll
-      for (int e = 0; e < EPV; ++e) jsd_push(zp[e], zq[e], cp, cq, dc, acc);
+      for (int j = 0; j < kJsdBatch; ++j) {          // masked in both rows: contributes exactly 0
+        const int idx = base + tid + j * kBlock;
+        const bool in = idx < v1;
+        const uint4 a = vp[in ? idx : v1 - 1], b = vq[in ? idx : v1 - 1];
+        xp[j] = make_uint4(in ? a.x : neutral.x, in ? a.y : neutral.y, in ? a.z : neutral.z, in ? a.w : neutral.w);
+        xq[j] = make_uint4(in ? b.x : neutral.x, in ? b.y : neutral.y, in ? b.z : neutral.z, in ? b.w : neutral.w);
+      }
+#pragma unroll
+      for (int j = 0; j < kJsdBatch; ++j) {
+        float zp[EPV], zq[EPV];
+        unpack<DT>(xp[j], zp);
+        unpack<DT>(xq[j], zq);
+#pragma unroll
+        for (int e = 0; e < EPV; e += 2) {
+          jsd_push(zp[e], zq[e], cp, cq, dc, acc);
+          jsd_push(zp[e + 1], zq[e + 1], cp, cq, dc, acc1);
+        }
+      }
     }
+    acc += acc1;
     if (s == S - 1 && tid == 0)
       for (int v = nv * EPV; v < V; ++v)
         jsd_push(load_elem<DT>(rp.ptr, v), load_elem<DT>(rq.ptr, v), cp, cq, dc, acc);
@@ -206,7 +261,7 @@ k_jsd(RowMap map, int S, Workspace ws, VerifyOut vout) {
 
   __shared__ float sha[kWaves];
   __shared__ int sh_last;
-  acc = wave_sum(acc);
+  acc = wave_sum_f(acc);
   const int lane = tid & 63, wave = tid >> 6;
   if (lane == 0) sha[wave] = acc;
   __syncthreads();
@@ -241,6 +296,7 @@ int pick_split(int rows, int V, int dt) {
   const int epv = dt == ADASD_BF16 ? 8 : 4;
   const int nv = V / epv;
   int S = (4096 + rows - 1) / (rows > 0 ? rows : 1);
+  if (const char* e = getenv("ADASD_SPLIT")) S = atoi(e);   // tuning experiments only
   int cap = nv / kBlock;            // at least one vector per thread and slice
   if (S > cap) S = cap;
   if (S > kMaxSplit) S = kMaxSplit;
@@ -248,14 +304,25 @@ int pick_split(int rows, int V, int dt) {
   return S;
 }
 
+// vectors per thread and batch: the smallest power of two that covers a slice in one batch, up to `most`
+static int pick_batch(int V, int dt, int S, int most) {
+  const int nv = V / (dt == ADASD_BF16 ? 8 : 4);
+  const int chunk = (nv + S - 1) / S, per_thread = (chunk + kBlock - 1) / kBlock;
+  int nb = 1;
+  while (nb < per_thread && nb < most) nb *= 2;
+  return nb;
+}
+
 hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Workspace& ws,
                            const VerifyOut& vout, const DraftOut& dout, hipStream_t st) {
   if (rows <= 0) return hipSuccess;
   dim3 grid(S, rows), block(kBlock);
-  if (dt == ADASD_BF16)
-    hipLaunchKernelGGL(k_rowstats<ADASD_BF16>, grid, block, 0, st, map, S, ws, vout, dout);
-  else
-    hipLaunchKernelGGL(k_rowstats<ADASD_F32>, grid, block, 0, st, map, S, ws, vout, dout);
+  const int nb = pick_batch(map.V, dt, S, 8);
+#define ADASD_ROW_CASE(DTV, NB) \
+  if (dt == DTV && nb == NB) hipLaunchKernelGGL((k_rowstats<DTV, NB>), grid, block, 0, st, map, S, ws, vout, dout);
+  ADASD_ROW_CASE(ADASD_BF16, 1) ADASD_ROW_CASE(ADASD_BF16, 2) ADASD_ROW_CASE(ADASD_BF16, 4) ADASD_ROW_CASE(ADASD_BF16, 8)
+  ADASD_ROW_CASE(ADASD_F32, 1) ADASD_ROW_CASE(ADASD_F32, 2) ADASD_ROW_CASE(ADASD_F32, 4) ADASD_ROW_CASE(ADASD_F32, 8)
+#undef ADASD_ROW_CASE
   return hipGetLastError();
 }
 
@@ -264,10 +331,12 @@ hipError_t launch_jsd(const RowMap& map, int dt, int S, const Workspace& ws, con
   const int positions = map.B * map.K;
   if (positions <= 0) return hipSuccess;
   dim3 grid(S, positions), block(kBlock);
-  if (dt == ADASD_BF16)
-    hipLaunchKernelGGL(k_jsd<ADASD_BF16>, grid, block, 0, st, map, S, ws, vout);
-  else
-    hipLaunchKernelGGL(k_jsd<ADASD_F32>, grid, block, 0, st, map, S, ws, vout);
+  const int nb = pick_batch(map.V, dt, S, 4);
+#define ADASD_JSD_CASE(DTV, NB) \
+  if (dt == DTV && nb == NB) hipLaunchKernelGGL((k_jsd<DTV, NB>), grid, block, 0, st, map, S, ws, vout);
+  ADASD_JSD_CASE(ADASD_BF16, 1) ADASD_JSD_CASE(ADASD_BF16, 2) ADASD_JSD_CASE(ADASD_BF16, 4)
+  ADASD_JSD_CASE(ADASD_F32, 1) ADASD_JSD_CASE(ADASD_F32, 2) ADASD_JSD_CASE(ADASD_F32, 4)
+#undef ADASD_JSD_CASE
   return hipGetLastError();
 }
 
