@@ -201,11 +201,10 @@ int adasd_draft_entropy(const void* draft_logits, adasd_dtype dt, int B, int V, 
   map.B = B;
   map.V = V;
   DraftOut dout{T_G, H_out, stop_out, step + 1 >= k_max ? 1 : 0};
-  VerifyOut vout{nullptr, nullptr, nullptr};
   hipStream_t st = (hipStream_t)stream;
   const int S = pick_split(B, V, (int)dt);
   Scope sc(5, st);
-  return launch_rowstats(map, (int)dt, B, S, ws, vout, dout, st) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
+  return launch_rowstats(map, (int)dt, B, S, ws, &dout, st) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
 }
 
 int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* stream) {
@@ -257,25 +256,6 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   map.B = B;
   map.V = V;
 
-  VerifyOut vout{a->H_p, a->H_q, a->d_js};
-  DraftOut dout{nullptr, nullptr, nullptr, 0};
-  int fNV = 0, fS = 0;
-  if (K > 0 && opt.stats_path == 2 && fused_plan(map, (int)a->dt, &fNV, &fS)) {
-    Scope sc(0, st);
-    if (launch_stats_fused(map, (int)a->dt, fNV, fS, g_spin_limit.load(), ws, vout, st) != hipSuccess) return ADASD_ERR_HIP;
-  } else if (K > 0) {
-    const int rows = B * K * 2;
-    const int S = pick_split(rows, V, (int)a->dt);
-    {
-      Scope sc(0, st);
-      if (launch_rowstats(map, (int)a->dt, rows, S, ws, vout, dout, st) != hipSuccess) return ADASD_ERR_HIP;
-    }
-    {
-      Scope sc(1, st);
-      if (launch_jsd(map, (int)a->dt, S, ws, vout, st) != hipSuccess) return ADASD_ERR_HIP;
-    }
-  }
-
   DecideArgs d{};
   d.map = map;
   d.dt = (int)a->dt;
@@ -303,6 +283,24 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   d.p_accept = a->p_accept;
   d.accept_mask = a->accept_mask;
   d.status = a->status;
+  VerifyOut vout{a->H_p, a->H_q, a->d_js};
+  int fNV = 0, fS = 0;
+  if (K > 0 && opt.stats_path == 2 && fused_plan(map, (int)a->dt, &fNV, &fS)) {
+    Scope sc(0, st);
+    if (launch_stats_fused(map, (int)a->dt, fNV, fS, g_spin_limit.load(), ws, vout, st) != hipSuccess) return ADASD_ERR_HIP;
+  } else if (K > 0) {
+    const int rows = B * K * 2;
+    const int S = pick_split(rows, V, (int)a->dt);
+    {
+      Scope sc(0, st);
+      if (launch_rowstats(map, (int)a->dt, rows, S, ws, nullptr, st) != hipSuccess) return ADASD_ERR_HIP;
+    }
+    {
+      Scope sc(1, st);
+      if (launch_jsd(map, (int)a->dt, S, ws, vout, st) != hipSuccess) return ADASD_ERR_HIP;
+    }
+    d.jsd_split = S;
+  }
   {
     Scope sc(2, st);
     if (launch_decide(d, ws, st) != hipSuccess) return ADASD_ERR_HIP;

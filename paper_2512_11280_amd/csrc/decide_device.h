@@ -1,0 +1,253 @@
+// Device code of the acceptance decisions of one sequence (Section 2.1.3, Section 4.4 and the
+// verification loop of Algorithm 1 of the paper), shared by the stand-alone decision kernel and by
+// the JS-distance kernel, whose last workgroup of a sequence runs it in place.
+#pragma once
+#include "internal.h"
+
+namespace adasd {
+
+// ---- reductions over half a wavefront (32 lanes) in double precision: rotations inside the rows of
+// 16 lanes on the two 32-bit halves, then one exchange between the two rows.  All 32 lanes get the result.
+template <int CTRL> __device__ __forceinline__ double dpp_rot_d(double v) {
+  const int lo = __double2loint(v), hi = __double2hiint(v);
+  return __hiloint2double(__builtin_amdgcn_update_dpp(0, hi, CTRL, 0xf, 0xf, false),
+                          __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ double half_sum_d(double v) {
+  v += dpp_rot_d<0x121>(v);
+  v += dpp_rot_d<0x122>(v);
+  v += dpp_rot_d<0x124>(v);
+  v += dpp_rot_d<0x128>(v);
+  return v + __shfl_xor(v, 16);
+}
+__device__ __forceinline__ double half_max_d(double v) {
+  v = fmax(v, dpp_rot_d<0x121>(v));
+  v = fmax(v, dpp_rot_d<0x122>(v));
+  v = fmax(v, dpp_rot_d<0x124>(v));
+  v = fmax(v, dpp_rot_d<0x128>(v));
+  return fmax(v, __shfl_xor(v, 16));
+}
+
+struct Kde {
+  double inv2h2;   // 1 / (2 h^2)
+  double log_norm; // ln(n h sqrt(2 pi)) - ln prior  (subtracted from the log kernel sum)
+};
+
+// Gaussian-kernel constants of a history list from its shifted moments (sum and sum of squares of
+// x - shift): sample variance with n-1, the bandwidth rule, the list-size prior.
+__device__ inline bool kde_constants(double s1, double s2, int n, int n_other, int bw_rule, Kde* out) {
+  const double var = (s2 - s1 * s1 / (double)n) / (double)(n - 1);
+  if (!(var > 0.0)) return false;
+  const double factor = bw_rule == 1 ? pow((double)n, -0.2) : pow(4.0 / (3.0 * (double)n), 0.2);
+  const double h = factor * sqrt(var);
+  out->inv2h2 = 1.0 / (2.0 * h * h);
+  const double prior = (double)n / (double)(n + n_other);
+  out->log_norm = log((double)n * h * 2.50662827463100050242) - log(prior);
+  return true;
+}
+
+// ln [ p(d | list) P(list) ] evaluated by half a wavefront: max-shifted log-sum-exp of the kernels.
+__device__ inline double half_log_joint(double d, const float* L, int n, const Kde& k) {
+  const int l32 = threadIdx.x & 31;
+  double tmax = -INFINITY;
+  for (int j = l32; j < n; j += 32) {
+    double e = d - (double)L[j];
+    tmax = fmax(tmax, -(e * e) * k.inv2h2);
+  }
+  tmax = half_max_d(tmax);
+  float acc = 0.f;
+  for (int j = l32; j < n; j += 32) {
+    double e = d - (double)L[j];
+    double t = -(e * e) * k.inv2h2 - tmax;            // <= 0
+    acc += ex2((float)(t * 1.44269504088896340736));  // e^t; terms below 2^-126 vanish
+  }
+  const double total = half_sum_d((double)acc);
+  return tmax + log(total) - k.log_norm;
+}
+
+struct DecideShared {
+  double mom[kWaves][4];            // per-wave shifted moments of the two lists
+  double lse2[ADASD_MAX_K][2];      // normalisers of the candidate positions (for the sampling plan)
+  uint8_t acc[ADASD_MAX_K];         // 1: position accepted
+  uint8_t bad[ADASD_MAX_K];
+  uint32_t status;
+};
+
+// The decisions of one sequence by one workgroup of 256 threads.
+template <int DT>
+__device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b, DecideShared& sh) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = tid & 31, grp = tid >> 5;
+  constexpr int kGroups = kBlock / 32;
+  const int K = a.map.K;
+  if (tid == 0) sh.status = 0;
+
+  int kb = K;
+  uint32_t st = 0;
+  if (a.map.draft_len) {
+    int raw = a.map.draft_len[b];
+    kb = min(max(raw, 0), K);
+    if (raw != kb) st |= ADASD_ST_BAD_LENGTH;
+  }
+
+  // ---- distances of the two-kernel path: add up the slices' partial sums (fixed order), correct the
+  // common scale to first order, take the root.  The weights were formed with the float roundings
+  // cp, cq of the normalisers, i.e. they are p(1+a), q(1+a') with a = ln2 (lse2_p - cp).
+  if (a.jsd_split > 0 && tid < kb) {
+    const size_t o = (size_t)b * K + tid;
+    const RowResult r0 = ws.rows[2 * o], r1 = ws.rows[2 * o + 1];
+    float d_out = NAN;
+    if (!(r0.bad || r1.bad)) {
+      double A = 0.0;
+      for (int j = 0; j < a.jsd_split; ++j)
+        A += (double)reinterpret_cast<const float*>(&ws.part2[o * kMaxSplit + j])[0];
+      const double c0 = kLn2 * (r0.lse2 - (double)(float)r0.lse2), c1 = kLn2 * (r1.lse2 - (double)(float)r1.lse2);
+      double D = 0.5 * A * (1.0 - 0.5 * (c0 + c1));   // bits
+      D = fmin(fmax(D, 0.0), 1.0);
+      d_out = (float)sqrt(D);
+    }
+    a.d_js[o] = d_out;
+  }
+  if (a.jsd_split > 0) __syncthreads();
+
+  // ---- Bayesian test set-up: both lists need enough samples and spread (else P(A|d) = 0).
+  // One pass over both lists (moments about the first element), one workgroup reduction.
+  const int min_n = a.kde_min_n < 2 ? 2 : a.kde_min_n;
+  int nA = 0, nR = 0;
+  const float* LA = nullptr;
+  const float* LR = nullptr;
+  if (a.LA && a.LR && a.nA && a.nR) {
+    nA = min(max(a.nA[b], 0), a.cap);
+    nR = min(max(a.nR[b], 0), a.cap);
+    LA = a.LA + (size_t)b * a.cap;
+    LR = a.LR + (size_t)b * a.cap;
+  }
+  bool kde_on = !a.relaxed_off && nA >= min_n && nR >= min_n;
+  Kde kA, kR;
+  if (kde_on) {          // uniform over the workgroup
+    const double cA = (double)LA[0], cR = (double)LR[0];
+    double m[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int j = tid; j < nA; j += kBlock) {
+      const double e = (double)LA[j] - cA;
+      m[0] += e;
+      m[1] += e * e;
+    }
+    for (int j = tid; j < nR; j += kBlock) {
+      const double e = (double)LR[j] - cR;
+      m[2] += e;
+      m[3] += e * e;
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      m[x] = half_sum_d(m[x]);
+      m[x] += __shfl_xor(m[x], 32);
+    }
+    if (lane == 0) {
+#pragma unroll
+      for (int x = 0; x < 4; ++x) sh.mom[wave][x] = m[x];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int x = 0; x < 4; ++x) m[x] = (sh.mom[0][x] + sh.mom[1][x]) + (sh.mom[2][x] + sh.mom[3][x]);
+    const bool okA = kde_constants(m[0], m[1], nA, nR, a.bw_rule, &kA);
+    const bool okR = kde_constants(m[2], m[3], nR, nA, a.bw_rule, &kR);
+    kde_on = okA && okR;
+  }
+
+  const uint32_t seq = a.seq_id ? a.seq_id[b] : (uint32_t)b;
+  const uint32_t rnd = a.round ? a.round[b] : a.round0;
+
+  // ---- half a wavefront per candidate position
+  for (int i = grp; i < K; i += kGroups) {
+    const size_t o = (size_t)b * K + i;
+    if (i >= kb) {
+      if (l32 == 0) {
+        if (a.H_p) a.H_p[o] = 0.f;
+        a.H_q[o] = 0.f;
+        a.d_js[o] = 0.f;
+        if (a.p_accept) a.p_accept[o] = 0.f;
+        if (a.accept_mask) a.accept_mask[o] = 0;
+        sh.acc[i] = 0;
+        sh.bad[i] = 0;
+      }
+      continue;
+    }
+    // everything the serial tail needs is requested now, so that it arrives behind the kernel sums
+    const int x = a.draft_tokens[o];
+    const bool x_ok = x >= 0 && x < a.map.V;
+    const char* prow = a.map.base[0] +
+        ((int64_t)b * a.map.seq_stride[0] + (int64_t)i * a.map.pos_stride[0]) * Elem<DT>::bytes;
+    const char* qrow = a.map.base[1] +
+        ((int64_t)b * a.map.seq_stride[1] + (int64_t)i * a.map.pos_stride[1]) * Elem<DT>::bytes;
+    const float zp = load_elem<DT>(prow, x_ok ? x : 0), zq = load_elem<DT>(qrow, x_ok ? x : 0);
+    const RowResult rp = ws.rows[2 * o], rq = ws.rows[2 * o + 1];
+    const bool bad = rp.bad || rq.bad;
+    const double d = (double)a.d_js[o];
+    double PA = 0.0;
+    if (!bad && kde_on) {
+      double ja = half_log_joint(d, LA, nA, kA);
+      double jr = half_log_joint(d, LR, nR, kR);
+      PA = 1.0 / (1.0 + exp(jr - ja));
+    }
+    if (l32 != 0) continue;
+    sh.lse2[i][0] = rp.lse2;
+    sh.lse2[i][1] = rq.lse2;
+    sh.bad[i] = bad;
+    if (bad) {
+      if (a.H_p) a.H_p[o] = NAN;
+      a.H_q[o] = NAN;
+      a.d_js[o] = NAN;
+      if (a.p_accept) a.p_accept[o] = NAN;
+      if (a.accept_mask) a.accept_mask[o] = 0;
+      sh.acc[i] = 0;
+      atomicOr(&sh.status, (uint32_t)ADASD_ST_NONFINITE);
+      continue;
+    }
+    const U4 r = philox4x32_10(0u, (uint32_t)i, rnd, seq, a.seed_lo, a.seed_hi);
+    const double u1 = ((double)(r.w[0] >> 8) + 0.5) * (1.0 / 16777216.0);
+    const double u2 = ((double)(r.w[1] >> 8) + 0.5) * (1.0 / 16777216.0);
+    // speculative-sampling test: accept with probability min(1, p(x)/q(x)), in the log domain
+    int base = 0;
+    if (!x_ok) {
+      atomicOr(&sh.status, (uint32_t)ADASD_ST_BAD_TOKEN);
+    } else {
+      double lp = (double)zp - rp.lse2 * kLn2;
+      double lq = (double)zq - rq.lse2 * kLn2;
+      double log_ratio = lp - lq;
+      if (log_ratio > 0.0) log_ratio = 0.0;
+      base = log(u1) < log_ratio;   // false for NaN (both probabilities zero)
+    }
+    const int relaxed = a.reject_rule == 1 ? (PA >= 0.5) : (u2 < PA);
+    if (a.p_accept) a.p_accept[o] = (float)PA;
+    if (a.accept_mask) a.accept_mask[o] = (uint8_t)(base | (relaxed << 1));
+    sh.acc[i] = (uint8_t)(base || relaxed);   // rejected only if both tests reject
+  }
+  __syncthreads();
+  if (tid != 0) return;
+
+  int r = kb;
+  for (int i = 0; i < kb; ++i)
+    if (!sh.acc[i]) {
+      r = i;
+      break;
+    }
+  a.n_accept[b] = r;
+  st |= sh.status;
+  SamplePlan plan;
+  plan.row = r;
+  plan.pad = 0;
+  if (r < kb) {
+    plan.residual = 1;
+    plan.valid = !sh.bad[r];
+    plan.lse2_p = sh.lse2[r][0];
+    plan.lse2_q = sh.lse2[r][1];
+  } else {
+    plan.residual = 0;   // bonus row: Gumbel-max needs no normaliser
+    plan.valid = 1;
+    plan.lse2_p = 0.0;
+    plan.lse2_q = 0.0;
+  }
+  ws.plan[b] = plan;
+  a.status[b] = st;
+}
+
+}  // namespace adasd

@@ -61,17 +61,17 @@ struct VerifyOut {
 
 int pick_split(int rows, int V, int dt);
 
+// dout: null in verify mode (the JS kernel folds the slice results), else the draft-entropy outputs
 hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Workspace& ws,
-                           const VerifyOut& vout, const DraftOut& dout, hipStream_t st);
+                           const DraftOut* dout, hipStream_t st);
 bool fused_plan(const RowMap& map, int dt, int* NV_out, int* S_out);
 hipError_t launch_stats_fused(const RowMap& map, int dt, int NV, int S, int spin_limit,
                               const Workspace& ws, const VerifyOut& vout, hipStream_t st);
-hipError_t launch_jsd(const RowMap& map, int dt, int S, const Workspace& ws, const VerifyOut& vout,
-                      hipStream_t st);
 
 struct DecideArgs {
   RowMap map;
   int32_t dt;
+  int32_t jsd_split;   // > 0: the distances are still per-slice partial sums of the JS kernel (that many per position)
   const int32_t* draft_tokens;
   // state (device pointers, may be null)
   int32_t cap;
@@ -94,6 +94,9 @@ struct DecideArgs {
   uint32_t* status;
 };
 hipError_t launch_decide(const DecideArgs& a, const Workspace& ws, hipStream_t st);
+// JS distance: per-slice partial sums (the decision kernel adds them up), rows and entropies
+hipError_t launch_jsd(const RowMap& map, int dt, int S, const Workspace& ws, const VerifyOut& vout,
+                      hipStream_t st);
 
 struct SampleArgs {
   RowMap map;

@@ -64,22 +64,16 @@ __device__ __forceinline__ void lse_push_vec(Lse& st, const uint4& q) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Pass 1: partial (m, s, u) of one slice of one row; last arrival finalises lse and entropy.
+// Pass 1: partial (m, s, u) of one slice of one row.
 // ---------------------------------------------------------------------------------------------
 template <int DT, int kRowBatch>   // kRowBatch: vectors per thread and batch
 __global__ void __launch_bounds__(kBlock)
-k_rowstats(RowMap map, int S, Workspace ws, VerifyOut vout, DraftOut dout) {
-  warm_kernargs<sizeof(RowMap) + sizeof(int) + sizeof(Workspace) + sizeof(VerifyOut) + sizeof(DraftOut)>();
+k_rowstats(RowMap map, int S, Workspace ws) {
+  warm_kernargs<sizeof(RowMap) + sizeof(int) + sizeof(Workspace)>();
   constexpr int EPV = Elem<DT>::per_vec;
   const int rho = blockIdx.y, s = blockIdx.x, tid = threadIdx.x;
   const RowRef r = locate_row<DT>(map, rho);
-  if (!r.active) {
-    if (map.K == 0 && s == 0 && tid == 0) {
-      dout.H_out[r.b] = 0.f;
-      if (dout.stop_out) dout.stop_out[r.b] = 0;
-    }
-    return;
-  }
+  if (!r.active) return;
   const int V = map.V;
   // Vector path: batches of kRowBatch vectors per thread are loaded up front (all loads of a batch in
   // flight at once), the batch's largest finite logit becomes the wavefront's reference if it exceeds
@@ -129,7 +123,6 @@ k_rowstats(RowMap map, int S, Workspace ws, VerifyOut vout, DraftOut dout) {
   }
 
   __shared__ Lse sh[kWaves];
-  __shared__ int sh_last;
   const int lane = tid & 63, wave = tid >> 6;
   if (lane == 0) sh[wave] = st;
   __syncthreads();
@@ -137,51 +130,56 @@ k_rowstats(RowMap map, int S, Workspace ws, VerifyOut vout, DraftOut dout) {
     Lse t = sh[0];
 #pragma unroll
     for (int w = 1; w < kWaves; ++w) t = lse_merge(t, sh[w]);
-    float* dst = reinterpret_cast<float*>(&ws.part1[(size_t)rho * kMaxSplit + s]);
-    st_agent(dst, t.m);
-    st_agent(dst + 1, t.s);
-    st_agent(dst + 2, t.u);
-    publish_barrier();
-    int ticket = atomicAdd(&ws.ticket1[rho], 1);
-    sh_last = (ticket == S - 1);
+    ws.part1[(size_t)rho * kMaxSplit + s] = make_float4(t.m, t.s, t.u, 0.f);   // folded by the next kernel
   }
-  __syncthreads();
-  if (!sh_last || wave != 0) return;
+}
 
+// Fold of the S slice results of one row by one wavefront (all lanes return the same): common
+// reference, plain sums, then the row's log2-sum-exp and entropy in double precision.
+__device__ __forceinline__ RowResult fold_row(const Workspace& ws, int rho, int S) {
+  const int lane = threadIdx.x & 63;
   Lse t = lse_empty();
   if (lane < S) {
-    const float* p = reinterpret_cast<const float*>(&ws.part1[(size_t)rho * kMaxSplit + lane]);
-    t.m = ld_agent(p);
-    t.s = ld_agent(p + 1);
-    t.u = ld_agent(p + 2);
+    const float4 p = ws.part1[(size_t)rho * kMaxSplit + lane];
+    t = Lse{p.x, p.y, p.z};
   }
-  t = wave_reduce(t);
-  if (lane != 0) return;
-  const bool ok = (t.s > 0.f) && (t.s < INFINITY) && (fabsf(t.u) < INFINITY) && (t.m > kNegHuge) &&
-                  (t.m < INFINITY);
+  const float M = wave_max_f(t.m), d = t.m - M, f = ex2(d);
+  const float sw = wave_sum_f(t.s * f), uw = wave_sum_f((t.u + d * t.s) * f);
+  const bool ok = (sw > 0.f) && (sw < INFINITY) && (fabsf(uw) < INFINITY) && (M > kNegHuge) && (M < INFINITY);
   RowResult res;
   if (ok) {
-    double l2s = log2((double)t.s);
-    res.lse2 = (double)t.m + l2s;
-    res.H = (float)(kLn2 * (l2s - (double)t.u / (double)t.s));
+    const double l2s = log2((double)sw);
+    res.lse2 = (double)M + l2s;
+    res.H = (float)(kLn2 * (l2s - (double)uw / (double)sw));
     res.bad = 0;
   } else {
     res.lse2 = NAN;
     res.H = NAN;
     res.bad = 1;
   }
-  ws.rows[rho] = res;
-  if (map.K > 0) {
-    float* H = r.which == 0 ? vout.H_p : vout.H_q;
-    if (H) H[(size_t)r.b * map.K + r.i] = res.H;
-  } else {
-    dout.H_out[r.b] = res.H;
-    if (dout.stop_out) {
-      bool over = dout.T_G ? (res.H > dout.T_G[r.b]) : false;
-      dout.stop_out[r.b] = (uint8_t)(over || dout.force_stop || res.bad);
+  return res;
+}
+
+// Draft-entropy epilogue (stop rule of Algorithm 1's drafting loop): one wavefront per row.
+__global__ void __launch_bounds__(kBlock) k_rows_finish(RowMap map, int S, Workspace ws, DraftOut dout) {
+  const int lane = threadIdx.x & 63, rho = blockIdx.x * kWaves + (threadIdx.x >> 6);
+  if (rho >= map.B) return;
+  const bool active = map.active ? (map.active[rho] != 0) : true;
+  if (!active) {
+    if (lane == 0) {
+      dout.H_out[rho] = 0.f;
+      if (dout.stop_out) dout.stop_out[rho] = 0;
     }
+    return;
   }
-  __hip_atomic_store(&ws.ticket1[rho], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const RowResult res = fold_row(ws, rho, S);
+  if (lane != 0) return;
+  ws.rows[rho] = res;
+  dout.H_out[rho] = res.H;
+  if (dout.stop_out) {
+    bool over = dout.T_G ? (res.H > dout.T_G[rho]) : false;
+    dout.stop_out[rho] = (uint8_t)(over || dout.force_stop || res.bad);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -208,35 +206,50 @@ __global__ void __launch_bounds__(kBlock)
 k_jsd(RowMap map, int S, Workspace ws, VerifyOut vout) {
   warm_kernargs<sizeof(RowMap) + sizeof(int) + sizeof(Workspace) + sizeof(VerifyOut)>();
   constexpr int EPV = Elem<DT>::per_vec;
-  const int pos = blockIdx.y, s = blockIdx.x, tid = threadIdx.x;
+  const int pos = blockIdx.y, s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ RowResult sh_row[2];
+  __shared__ float sha[kWaves];
   const RowRef rp = locate_row<DT>(map, 2 * pos), rq = locate_row<DT>(map, 2 * pos + 1);
   if (!rp.active) return;
-  const RowResult resp = ws.rows[2 * pos], resq = ws.rows[2 * pos + 1];
-  if (resp.bad || resq.bad) {
-    if (s == 0 && tid == 0) vout.d_js[pos] = NAN;
-    return;
+  const int V = map.V;
+  const bool vec_path = aligned16(rp.ptr) && aligned16(rq.ptr);
+  const int nv = V / EPV;
+  const int chunk = (nv + S - 1) / S, v0 = min(s * chunk, nv), v1 = min(v0 + chunk, nv);
+  const uint4* vp = reinterpret_cast<const uint4*>(rp.ptr);
+  const uint4* vq = reinterpret_cast<const uint4*>(rq.ptr);
+  const uint4 neutral = neutral_vec<DT>();
+  uint4 xp[kJsdBatch], xq[kJsdBatch];
+  // one batch of vector pairs: all loads in flight at once; a pair masked in both rows contributes 0
+  auto load_batch = [&](int base) {
+#pragma unroll
+    for (int j = 0; j < kJsdBatch; ++j) {
+      const int idx = base + tid + j * kBlock;
+      const bool in = idx < v1;
+      const uint4 a = vp[in ? idx : v1 - 1], b = vq[in ? idx : v1 - 1];
+      xp[j] = make_uint4(in ? a.x : neutral.x, in ? a.y : neutral.y, in ? a.z : neutral.z, in ? a.w : neutral.w);
+      xq[j] = make_uint4(in ? b.x : neutral.x, in ? b.y : neutral.y, in ? b.z : neutral.z, in ? b.w : neutral.w);
+    }
+  };
+  // the first batch is requested before anything else: it does not depend on the normalisers
+  if (vec_path && v0 < v1) load_batch(v0);
+
+  // both rows' slice results are folded by every workgroup of the position, the same way
+  if (wave < 2) {
+    const RowResult res = fold_row(ws, 2 * pos + wave, S);
+    if (lane == 0) sh_row[wave] = res;
   }
+  __syncthreads();
+  const RowResult resp = sh_row[0], resq = sh_row[1];
+  const bool bad = resp.bad || resq.bad;
   const float cp = (float)resp.lse2, cq = (float)resq.lse2;
   const float dc = (float)(resq.lse2 - resp.lse2);
-  const int V = map.V;
   float acc = 0.f;
-  if (aligned16(rp.ptr) && aligned16(rq.ptr)) {
-    const int nv = V / EPV;
-    const int chunk = (nv + S - 1) / S, v0 = min(s * chunk, nv), v1 = min(v0 + chunk, nv);
-    const uint4* vp = reinterpret_cast<const uint4*>(rp.ptr);
-    const uint4* vq = reinterpret_cast<const uint4*>(rq.ptr);
-    const uint4 neutral = neutral_vec<DT>();
+  if (bad) {
+    // nothing to add up: the decision kernel reports the distance as NaN
+  } else if (vec_path) {
     float acc1 = 0.f;
     for (int base = v0; base < v1; base += kJsdBatch * kBlock) {
-      uint4 xp[kJsdBatch], xq[kJsdBatch];
-#pragma unroll
-      for (int j = 0; j < kJsdBatch; ++j) {          // masked in both rows: contributes exactly 0
-        const int idx = base + tid + j * kBlock;
-        const bool in = idx < v1;
-        const uint4 a = vp[in ? idx : v1 - 1], b = vq[in ? idx : v1 - 1];
-        xp[j] = make_uint4(in ? a.x : neutral.x, in ? a.y : neutral.y, in ? a.z : neutral.z, in ? a.w : neutral.w);
-        xq[j] = make_uint4(in ? b.x : neutral.x, in ? b.y : neutral.y, in ? b.z : neutral.z, in ? b.w : neutral.w);
-      }
+      if (base != v0) load_batch(base);
 #pragma unroll
       for (int j = 0; j < kJsdBatch; ++j) {
         float zp[EPV], zq[EPV];
@@ -259,35 +272,22 @@ k_jsd(RowMap map, int S, Workspace ws, VerifyOut vout) {
       jsd_push(load_elem<DT>(rp.ptr, v), load_elem<DT>(rq.ptr, v), cp, cq, dc, acc);
   }
 
-  __shared__ float sha[kWaves];
-  __shared__ int sh_last;
   acc = wave_sum_f(acc);
-  const int lane = tid & 63, wave = tid >> 6;
   if (lane == 0) sha[wave] = acc;
   __syncthreads();
   if (tid == 0) {
     float t = 0.f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) t += sha[w];
-    st_agent(reinterpret_cast<float*>(&ws.part2[(size_t)pos * kMaxSplit + s]), t);
-    publish_barrier();
-    int ticket = atomicAdd(&ws.ticket2[pos], 1);
-    sh_last = (ticket == S - 1);
+    // partial sum of this slice: added up, corrected and turned into the distance by the decision kernel
+    reinterpret_cast<float*>(&ws.part2[(size_t)pos * kMaxSplit + s])[0] = t;
+    if (s == 0) {        // the position's rows and entropies, once
+      ws.rows[2 * pos] = resp;
+      ws.rows[2 * pos + 1] = resq;
+      if (vout.H_p) vout.H_p[pos] = resp.H;
+      vout.H_q[pos] = resq.H;
+    }
   }
-  __syncthreads();
-  if (!sh_last || wave != 0) return;
-
-  double A = 0.0;
-  if (lane < S) A = (double)ld_agent(reinterpret_cast<const float*>(&ws.part2[(size_t)pos * kMaxSplit + lane]));
-  A = wave_sum(A);
-  if (lane != 0) return;
-  // The weights b were formed with the float roundings cp, cq of the normalisers, i.e. they are
-  // p(1+a), q(1+a') with a = ln2 (lse2_p - cp); the sum scales by 1 + (a+a')/2 to first order.
-  const double a = kLn2 * (resp.lse2 - (double)cp), a2 = kLn2 * (resq.lse2 - (double)cq);
-  double D = 0.5 * A * (1.0 - 0.5 * (a + a2));   // bits
-  D = fmin(fmax(D, 0.0), 1.0);
-  vout.d_js[pos] = (float)sqrt(D);
-  __hip_atomic_store(&ws.ticket2[pos], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace
@@ -314,15 +314,17 @@ static int pick_batch(int V, int dt, int S, int most) {
 }
 
 hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Workspace& ws,
-                           const VerifyOut& vout, const DraftOut& dout, hipStream_t st) {
+                           const DraftOut* dout, hipStream_t st) {
   if (rows <= 0) return hipSuccess;
   dim3 grid(S, rows), block(kBlock);
   const int nb = pick_batch(map.V, dt, S, 8);
 #define ADASD_ROW_CASE(DTV, NB) \
-  if (dt == DTV && nb == NB) hipLaunchKernelGGL((k_rowstats<DTV, NB>), grid, block, 0, st, map, S, ws, vout, dout);
+  if (dt == DTV && nb == NB) hipLaunchKernelGGL((k_rowstats<DTV, NB>), grid, block, 0, st, map, S, ws);
   ADASD_ROW_CASE(ADASD_BF16, 1) ADASD_ROW_CASE(ADASD_BF16, 2) ADASD_ROW_CASE(ADASD_BF16, 4) ADASD_ROW_CASE(ADASD_BF16, 8)
   ADASD_ROW_CASE(ADASD_F32, 1) ADASD_ROW_CASE(ADASD_F32, 2) ADASD_ROW_CASE(ADASD_F32, 4) ADASD_ROW_CASE(ADASD_F32, 8)
 #undef ADASD_ROW_CASE
+  if (dout)    // draft-entropy mode: rows are finalised by a second, small kernel
+    hipLaunchKernelGGL(k_rows_finish, dim3((rows + kWaves - 1) / kWaves), block, 0, st, map, S, ws, *dout);
   return hipGetLastError();
 }
 
