@@ -21,6 +21,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the statistics stage on this workload, from the rocprofv3 counter runs kept
+# under profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a plain copy of known
+# size): k_rowstats 131.63 MB + 0.13 MB, k_jsd 132.94 MB + 0.08 MB.  Only valid for the default path.
+STAGE_TRAFFIC_BYTES = 264.78e6
 B, K, V = 32, 8, 128256
 N_SETS = 4                     # 4 x 139.5 MB of logits
 LIST_CAP = 8192
@@ -34,6 +38,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sets", type=int, default=N_SETS)
     ap.add_argument("--stats-path", type=int, default=0, help="0 library default, 1 two-kernel path, 2 single-read kernel")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device-to-device copy of known size (counter calibration for rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (sequences are independent, so the "
@@ -63,6 +69,12 @@ def main():
     torch.cuda.synchronize()
 
     opts = am.Options(stats_path=args.stats_path)
+    if args.calibrate_copy:
+        src = sets[0][0]
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # one elementwise copy kernel: reads and writes src.nbytes
+        torch.cuda.synchronize()
+        print(f"calibration copy: {src.numel() * src.element_size()} bytes read and written", file=sys.stderr)
 
     def step(i):
         t, d, x, seed = sets[i % len(sets)]
@@ -82,9 +94,10 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     positions_per_s = B * K * args.steps / elapsed
 
-    # ---- the same steps again with HIP events around each kernel class (library-side, on the
-    #      launch stream): per-kernel durations for the roofline figure
-    am.profile_enable(args.steps)
+    # ---- the same steps again with HIP events carried by the kernel launches themselves (library
+    #      side, on the launch stream; the dispatch stamps them at its start and end): per-kernel
+    #      durations for the roofline figure
+    am.profile_enable(2 * args.steps + 8)
     state.load(host0.state)
     torch.cuda.synchronize()
     for i in range(args.steps):
@@ -95,16 +108,21 @@ def main():
     for c, name in enumerate(names):
         ms, n = am.profile_read(c)
         if n:
-            kern_us[name] = ms / n * 1e3
+            kern_us[name] = ms / args.steps * 1e3       # per step (a class may hold two kernels)
     am.profile_disable()
     mean_accept = float(out.n_accept.float().mean().item())
 
     # Algorithmic bytes of one launch of the statistics stage: every target and draft logit of the
-    # B*k verified positions once.  While the stage is two kernels (normalisers, then JS distance)
-    # the second read of the same bytes is not counted, so the fraction is against ONE read.
+    # B*k verified positions once (513 024 B per position).  The stage is two kernels (normalisers,
+    # then JS distance) that each stream those bytes; the second read is not counted, so the stage's
+    # fraction is against ONE read.  Each kernel alone is also given against the bytes it streams.
     algo_bytes = 2 * V * 2 * B * K
     stats_us = kern_us.get("row_stats", 0.0) + kern_us.get("jsd", 0.0)
     achieved = algo_bytes / (stats_us * 1e-6) / 1e9 if stats_us > 0 else 0.0
+    per_kernel = {name: {"kernel_us": kern_us[name], "streamed_bytes": algo_bytes,
+                         "GBps": algo_bytes / (kern_us[name] * 1e-6) / 1e9,
+                         "frac": algo_bytes / (kern_us[name] * 1e-6) / 1e9 / HBM_PEAK_GBS}
+                  for name in ("row_stats", "jsd") if name in kern_us}
 
     # ---- draft-side call (one [B, V] row block per drafted token), reported on the side
     rows = sets[0][1][:, 0]
@@ -126,7 +144,7 @@ def main():
         from oracle import load_oracle
         ora = load_oracle()
         s = host0.state
-        reps = 3
+        reps = 12                      # about 10 s of CPU work over the threads
         c0 = time.perf_counter()
         for r in range(reps):
             ora.verify(host0.target, host0.draft, host0.draft_tokens.numpy(), LA=s["LA"], LR=s["LR"],
@@ -154,10 +172,12 @@ def main():
                                f"{len(sets)} rotating seeded input sets, history lists 64+64 per sequence",
                    "step": "adasd_verify + adasd_update_thresholds"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "k_stats_fused" if "jsd" not in kern_us else "k_rowstats + k_jsd",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": STAGE_TRAFFIC_BYTES if ("jsd" in kern_us and args.stats_path in (0, 1)) else None,
+                     "kernel": "k_stats_pipe + k_stats_finish" if "jsd" not in kern_us else "k_rowstats + k_jsd",
                      "algorithmic_bytes": algo_bytes,
-                     "kernel_us": stats_us},
+                     "kernel_us": stats_us,
+                     "per_kernel": per_kernel},
         "cpu_baseline": cpu,
         "kernel_us": kern_us,
         "draft_entropy_us_per_call": draft_us,

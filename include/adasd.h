@@ -204,11 +204,13 @@ int adasd_update_thresholds(const adasd_state *st /* host */, int k_max, const i
 /*
  * Optional kernel timing for benchmarks (host side only; not for production loops).
  * adasd_profile_enable(n) creates n pairs of HIP events per kernel class and makes the entry points
- * record them around their kernels; adasd_profile_read waits for the recorded events and returns the
- * summed duration and launch count of one class since the last enable; adasd_profile_disable frees
- * the events.  Kernel classes: 0 row statistics (normalisers + entropy; the fused kernel also
- * produces the JS distance and then class 1 stays empty), 1 JS distance (two-pass form), 2 decision,
- * 3 token sampling, 4 state update, 5 draft entropy.
+ * hand one pair to each kernel launch (the dispatch stamps them at its start and end, so the
+ * durations hold no launch or queueing time); adasd_profile_read waits for the recorded events and
+ * returns the summed duration and the number of kernels of one class since the last enable;
+ * adasd_profile_disable frees the events.  Kernel classes: 0 row statistics (normalisers + entropy;
+ * with stats_path 2 the single-read kernel and its finalisation, class 1 then stays empty),
+ * 1 JS distance (two-kernel path), 2 decision, 3 token sampling, 4 state update, 5 draft entropy
+ * (two kernels per call).
  */
 int adasd_profile_enable(int max_launches);
 int adasd_profile_read(int kernel_class, double *total_ms /* host */, int *launches /* host */);

@@ -27,24 +27,25 @@ struct Profiler {
   int used[kClasses] = {0, 0, 0, 0, 0, 0};
 } g_prof;
 
-struct Scope {   // records a start event now and a stop event at destruction
-  int cls;
-  hipStream_t st;
-  int slot = -1;
-  Scope(int c, hipStream_t s) : cls(c), st(s) {
-    if (!g_prof.on) return;
-    std::lock_guard<std::mutex> lk(g_prof.mu);
-    if (g_prof.used[cls] < g_prof.cap) {
-      slot = g_prof.used[cls]++;
-      (void)hipEventRecord(g_prof.start[cls][slot], st);
-    }
-  }
-  ~Scope() {
-    if (slot >= 0) (void)hipEventRecord(g_prof.stop[cls][slot], st);
-  }
+thread_local int t_class = -1;   // kernel class of the timing scope that is open on this thread
+
+struct Scope {   // the kernels launched while it lives are timed under class c
+  int prev;
+  Scope(int c, hipStream_t) : prev(t_class) { t_class = c; }
+  ~Scope() { t_class = prev; }
 };
 
 }  // namespace
+
+bool profile_take_events(hipEvent_t* start, hipEvent_t* stop) {
+  if (!g_prof.on || t_class < 0) return false;
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  if (g_prof.used[t_class] >= g_prof.cap) return false;
+  const int slot = g_prof.used[t_class]++;
+  *start = g_prof.start[t_class][slot];
+  *stop = g_prof.stop[t_class][slot];
+  return true;
+}
 
 namespace {
 constexpr size_t kHeaderBytes = (65536 + 32768 + 32768) * sizeof(int32_t);

@@ -76,21 +76,21 @@ __global__ void __launch_bounds__(256) k_zero(uint32_t* p, size_t n) {
 hipError_t launch_decide(const DecideArgs& a, const Workspace& ws, hipStream_t st) {
   if (a.map.B <= 0) return hipSuccess;
   if (a.dt == ADASD_BF16)
-    hipLaunchKernelGGL(k_decide<ADASD_BF16>, dim3(a.map.B), dim3(kBlock), 0, st, a, ws);
+    launch_kernel(k_decide<ADASD_BF16>, dim3(a.map.B), dim3(kBlock), st, a, ws);
   else
-    hipLaunchKernelGGL(k_decide<ADASD_F32>, dim3(a.map.B), dim3(kBlock), 0, st, a, ws);
+    launch_kernel(k_decide<ADASD_F32>, dim3(a.map.B), dim3(kBlock), st, a, ws);
   return hipGetLastError();
 }
 
 hipError_t launch_update(const UpdateArgs& a, hipStream_t st) {
   if (a.B <= 0) return hipSuccess;
-  hipLaunchKernelGGL(k_update, dim3((a.B + 63) / 64), dim3(64), 0, st, a);
+  launch_kernel(k_update, dim3((a.B + 63) / 64), dim3(64), st, a);
   return hipGetLastError();
 }
 
 hipError_t launch_state_init(const UpdateArgs& a, hipStream_t st) {
   if (a.B <= 0) return hipSuccess;
-  hipLaunchKernelGGL(k_state_init, dim3((a.B + 63) / 64), dim3(64), 0, st, a);
+  launch_kernel(k_state_init, dim3((a.B + 63) / 64), dim3(64), st, a);
   return hipGetLastError();
 }
 
@@ -99,7 +99,7 @@ hipError_t launch_zero(void* p, size_t bytes, hipStream_t st) {
   if (n == 0) return hipSuccess;
   int blocks = (int)((n + 255) / 256);
   if (blocks > 1024) blocks = 1024;
-  hipLaunchKernelGGL(k_zero, dim3(blocks), dim3(256), 0, st, (uint32_t*)p, n);
+  launch_kernel(k_zero, dim3(blocks), dim3(256), st, (uint32_t*)p, n);
   return hipGetLastError();
 }
 

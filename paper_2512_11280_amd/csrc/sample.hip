@@ -360,8 +360,8 @@ __global__ void __launch_bounds__(kBlock) k_sample(SampleArgs a, int S, Workspac
 hipError_t launch_sample(const SampleArgs& a, int S, const Workspace& ws, hipStream_t st) {
   if (a.map.B <= 0) return hipSuccess;
   dim3 grid(S, a.map.B), block(kBlock);
-  if (a.dt == ADASD_BF16) hipLaunchKernelGGL(k_sample<ADASD_BF16>, grid, block, 0, st, a, S, ws);
-  else hipLaunchKernelGGL(k_sample<ADASD_F32>, grid, block, 0, st, a, S, ws);
+  if (a.dt == ADASD_BF16) launch_kernel(k_sample<ADASD_BF16>, grid, block, st, a, S, ws);
+  else launch_kernel(k_sample<ADASD_F32>, grid, block, st, a, S, ws);
   return hipGetLastError();
 }
 

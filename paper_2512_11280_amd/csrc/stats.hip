@@ -319,12 +319,12 @@ hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Wor
   dim3 grid(S, rows), block(kBlock);
   const int nb = pick_batch(map.V, dt, S, 8);
 #define ADASD_ROW_CASE(DTV, NB) \
-  if (dt == DTV && nb == NB) hipLaunchKernelGGL((k_rowstats<DTV, NB>), grid, block, 0, st, map, S, ws);
+  if (dt == DTV && nb == NB) launch_kernel((k_rowstats<DTV, NB>), grid, block, st, map, S, ws);
   ADASD_ROW_CASE(ADASD_BF16, 1) ADASD_ROW_CASE(ADASD_BF16, 2) ADASD_ROW_CASE(ADASD_BF16, 4) ADASD_ROW_CASE(ADASD_BF16, 8)
   ADASD_ROW_CASE(ADASD_F32, 1) ADASD_ROW_CASE(ADASD_F32, 2) ADASD_ROW_CASE(ADASD_F32, 4) ADASD_ROW_CASE(ADASD_F32, 8)
 #undef ADASD_ROW_CASE
   if (dout)    // draft-entropy mode: rows are finalised by a second, small kernel
-    hipLaunchKernelGGL(k_rows_finish, dim3((rows + kWaves - 1) / kWaves), block, 0, st, map, S, ws, *dout);
+    launch_kernel(k_rows_finish, dim3((rows + kWaves - 1) / kWaves), block, st, map, S, ws, *dout);
   return hipGetLastError();
 }
 
@@ -335,7 +335,7 @@ hipError_t launch_jsd(const RowMap& map, int dt, int S, const Workspace& ws, con
   dim3 grid(S, positions), block(kBlock);
   const int nb = pick_batch(map.V, dt, S, 4);
 #define ADASD_JSD_CASE(DTV, NB) \
-  if (dt == DTV && nb == NB) hipLaunchKernelGGL((k_jsd<DTV, NB>), grid, block, 0, st, map, S, ws, vout);
+  if (dt == DTV && nb == NB) launch_kernel((k_jsd<DTV, NB>), grid, block, st, map, S, ws, vout);
   ADASD_JSD_CASE(ADASD_BF16, 1) ADASD_JSD_CASE(ADASD_BF16, 2) ADASD_JSD_CASE(ADASD_BF16, 4)
   ADASD_JSD_CASE(ADASD_F32, 1) ADASD_JSD_CASE(ADASD_F32, 2) ADASD_JSD_CASE(ADASD_F32, 4)
 #undef ADASD_JSD_CASE

@@ -677,8 +677,8 @@ hipError_t launch_pipe(const RowMap& map, PipeGeom g, const Workspace& ws, const
   const int need = (g.items + ticks - 1) / ticks;
   G = (need + unit - 1) / unit * unit;
   g.pos_step = G / g.S;
-  hipLaunchKernelGGL((k_stats_pipe<DT, NV>), dim3(G), dim3(kBlock), 0, st, map, g, ws);
-  hipLaunchKernelGGL(k_stats_finish, dim3((g.P + kWaves - 1) / kWaves), dim3(kBlock), 0, st, map, g, ws, vout);
+  launch_kernel((k_stats_pipe<DT, NV>), dim3(G), dim3(kBlock), st, map, g, ws);
+  launch_kernel(k_stats_finish, dim3((g.P + kWaves - 1) / kWaves), dim3(kBlock), st, map, g, ws, vout);
   return hipGetLastError();
 }
 
