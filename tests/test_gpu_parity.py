@@ -85,6 +85,39 @@ def test_config_large_reduced(am, wl, oracle, path):
     _report("large(B=6,k=16,V=152064)", rep)
 
 
+def test_headline_workload_full_size(am, wl, oracle, path):
+    """The exact shape, generator, list capacity and launch configuration that bench.py times
+    (B=32, k=8, V=128256, bf16): every output of every sequence against the oracle."""
+    batch = wl.config_batched(seed=wl.DEFAULT_SEED + 2, B=32, k=8, V=128256, cap=8192)
+    out, _, _ = G.run_gpu(am, batch, stats_path=path)
+    ref = G.run_oracle(oracle, batch)
+    rep = G.compare_verify(out, ref)
+    _report("headline(B=32,k=8,V=128256)", rep)
+    assert 0 < ref["n_accept"].mean() < 8
+
+
+def test_large_workload_full_size_sampled_sequences(am, wl, oracle):
+    """B=128, k=16, V=152064 on the GPU in one call; the oracle redoes every 16th sequence (sequences
+    are independent: own lists, own Philox stream selected by the sequence id)."""
+    batch = wl.config_large(B=128, k=16)
+    out, _, _ = G.run_gpu(am, batch)
+    pick = list(range(0, 128, 16))
+    sub = wl.VerifyBatch(target=batch.target[pick], draft=batch.draft[pick],
+                         draft_tokens=batch.draft_tokens[pick],
+                         draft_len=None if batch.draft_len is None else batch.draft_len[pick],
+                         state={k: v[pick] for k, v in batch.state.items()},
+                         seed=batch.seed, round0=batch.round0)
+    ref = G.run_oracle(oracle, sub, seq_id=pick)
+
+    class Picked:
+        pass
+    got = Picked()
+    for name in ("n_accept", "next_token", "H_p", "H_q", "d_js", "p_accept", "accept_mask", "status"):
+        setattr(got, name, getattr(out, name)[pick])
+    rep = G.compare_verify(got, ref)
+    _report("large(B=128,k=16,V=152064), 8 sampled sequences", rep)
+
+
 def test_ragged_lengths_sequence_ids_and_rounds(am, wl, oracle, path):
     batch = wl.config_batched(B=6, k=5, V=32003, seed=99)       # V not a multiple of 8: scalar tail
     batch.draft_len = torch.tensor([0, 1, 5, 3, 2, 5], dtype=torch.int32)
