@@ -217,10 +217,11 @@ int adasd_profile_read(int kernel_class, double *total_ms /* host */, int *launc
 int adasd_profile_disable(void);
 
 /*
- * Test hook for the fused statistics kernel's bounded wait: its workgroups poll an arrival mask at
- * most `polls` times (default 65536, roughly 15 ms) before they stop waiting and recompute the missing
- * slices themselves, which gives bit-identical results.  0 makes every workgroup take that path at
- * once; tests use it to exercise the path without any wave ever spinning for long.
+ * Test hook for the bounded waits of the single-read statistics kernel (stats_path 2): a workgroup
+ * polls for the other workgroups' results at most `polls` times (default 65536, roughly 15 ms)
+ * before it stops waiting and recomputes them itself, which gives bit-identical results.  0 makes
+ * every workgroup take that path at once; tests use it to exercise the path without any wave ever
+ * spinning for long.
  */
 int adasd_set_spin_limit(int polls);
 

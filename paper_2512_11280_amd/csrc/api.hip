@@ -3,8 +3,6 @@
 #include <mutex>
 #include <vector>
 
-#include <cstdlib>
-
 #include "internal.h"
 
 namespace adasd {
@@ -83,7 +81,7 @@ size_t workspace_layout(size_t ws_bytes, Workspace* ws, void* base) {
       off = align_up(off + bytes, 256);
       return p + at;
     };
-    // arrival counters of the two-pass and sampling kernels: fixed size, sized for the compiled limits
+    // arrival counters (the sampling kernel uses ticket3; the others are spare): fixed size, sized for the compiled limits
     ws->ticket1 = reinterpret_cast<int32_t*>(take(65536 * sizeof(int32_t)));
     ws->ticket2 = reinterpret_cast<int32_t*>(take(32768 * sizeof(int32_t)));
     ws->ticket3 = reinterpret_cast<int32_t*>(take(32768 * sizeof(int32_t)));
@@ -320,7 +318,6 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   // about two 16-byte vectors per thread: enough workgroups to cover the chip for a handful of rows
   const int nvec = V / ((int)a->dt == ADASD_BF16 ? 8 : 4);
   int S3 = (nvec + 2 * kBlock - 1) / (2 * kBlock);
-  if (const char* e = getenv("ADASD_SPLIT3")) S3 = atoi(e);   // tuning experiments only
   if (S3 < 1) S3 = 1;
   if (S3 > kMaxSampleSplit) S3 = kMaxSampleSplit;
   {

@@ -38,11 +38,14 @@ struct Kde {
 __device__ inline bool kde_constants(double s1, double s2, int n, int n_other, int bw_rule, Kde* out) {
   const double var = (s2 - s1 * s1 / (double)n) / (double)(n - 1);
   if (!(var > 0.0)) return false;
-  const double factor = bw_rule == 1 ? pow((double)n, -0.2) : pow(4.0 / (3.0 * (double)n), 0.2);
+  // x^(1/5) through the hardware exp2 / log2 (relative error about 1e-7: far inside what the
+  // posterior's tolerance asks of the bandwidth)
+  const float base = bw_rule == 1 ? 1.0f / (float)n : 4.0f / (3.0f * (float)n);
+  const double factor = (double)ex2((float)(0.2 * log2_acc(base)));
   const double h = factor * sqrt(var);
   out->inv2h2 = 1.0 / (2.0 * h * h);
-  const double prior = (double)n / (double)(n + n_other);
-  out->log_norm = log((double)n * h * 2.50662827463100050242) - log(prior);
+  const float prior = (float)n / (float)(n + n_other);
+  out->log_norm = kLn2 * (log2_acc((float)((double)n * h * 2.50662827463100050242)) - log2_acc(prior));
   return true;
 }
 
@@ -62,7 +65,7 @@ __device__ inline double half_log_joint(double d, const float* L, int n, const K
     acc += ex2((float)(t * 1.44269504088896340736));  // e^t; terms below 2^-126 vanish
   }
   const double total = half_sum_d((double)acc);
-  return tmax + log(total) - k.log_norm;
+  return tmax + kLn2 * log2_acc((float)total) - k.log_norm;
 }
 
 struct DecideShared {
@@ -89,25 +92,46 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
     if (raw != kb) st |= ADASD_ST_BAD_LENGTH;
   }
 
-  // ---- distances of the two-kernel path: add up the slices' partial sums (fixed order), correct the
-  // common scale to first order, take the root.  The weights were formed with the float roundings
-  // cp, cq of the normalisers, i.e. they are p(1+a), q(1+a') with a = ln2 (lse2_p - cp).
-  if (a.jsd_split > 0 && tid < kb) {
-    const size_t o = (size_t)b * K + tid;
-    const RowResult r0 = ws.rows[2 * o], r1 = ws.rows[2 * o + 1];
-    float d_out = NAN;
-    if (!(r0.bad || r1.bad)) {
-      double A = 0.0;
-      for (int j = 0; j < a.jsd_split; ++j)
-        A += (double)reinterpret_cast<const float*>(&ws.part2[o * kMaxSplit + j])[0];
-      const double c0 = kLn2 * (r0.lse2 - (double)(float)r0.lse2), c1 = kLn2 * (r1.lse2 - (double)(float)r1.lse2);
-      double D = 0.5 * A * (1.0 - 0.5 * (c0 + c1));   // bits
-      D = fmin(fmax(D, 0.0), 1.0);
-      d_out = (float)sqrt(D);
+  const uint32_t seq = a.seq_id ? a.seq_id[b] : (uint32_t)b;
+  const uint32_t rnd = a.round ? a.round[b] : a.round0;
+
+  // Everything a candidate position needs from memory, and its two uniforms.  The first position of
+  // each group is requested before the list moments are formed, so the two chains of dependent
+  // loads (token -> its logits, list lengths -> samples) run side by side.
+  struct PosLoad {
+    int x;
+    bool x_ok;
+    float zp, zq, p0, p1;
+    RowResult rp, rq;
+    double log_u1, u2;
+  };
+  auto load_pos = [&](int i) {
+    PosLoad L;
+    const size_t o = (size_t)b * K + i;
+    L.x = a.draft_tokens[o];
+    L.x_ok = L.x >= 0 && L.x < a.map.V;
+    const char* prow = a.map.base[0] +
+        ((int64_t)b * a.map.seq_stride[0] + (int64_t)i * a.map.pos_stride[0]) * Elem<DT>::bytes;
+    const char* qrow = a.map.base[1] +
+        ((int64_t)b * a.map.seq_stride[1] + (int64_t)i * a.map.pos_stride[1]) * Elem<DT>::bytes;
+    L.zp = load_elem<DT>(prow, L.x_ok ? L.x : 0);
+    L.zq = load_elem<DT>(qrow, L.x_ok ? L.x : 0);
+    L.rp = ws.rows[2 * o];
+    L.rq = ws.rows[2 * o + 1];
+    L.p0 = L.p1 = 0.f;
+    if (a.jsd_split > 0) {
+      const float* part = reinterpret_cast<const float*>(ws.part2 + o * kMaxSplit);
+      L.p0 = l32 < a.jsd_split ? part[2 * l32] : 0.f;
+      L.p1 = l32 + 32 < a.jsd_split ? part[2 * (l32 + 32)] : 0.f;
     }
-    a.d_js[o] = d_out;
-  }
-  if (a.jsd_split > 0) __syncthreads();
+    const U4 r = philox4x32_10(0u, (uint32_t)i, rnd, seq, a.seed_lo, a.seed_hi);
+    // u1 = (w + 0.5) / 2^24 rounded to float: 3e-8 relative, i.e. 3e-8 absolute on its logarithm
+    L.log_u1 = kLn2 * log2_acc((float)(((double)(r.w[0] >> 8) + 0.5) * (1.0 / 16777216.0)));
+    L.u2 = ((double)(r.w[1] >> 8) + 0.5) * (1.0 / 16777216.0);
+    return L;
+  };
+  PosLoad first;
+  if (grp < kb) first = load_pos(grp);
 
   // ---- Bayesian test set-up: both lists need enough samples and spread (else P(A|d) = 0).
   // One pass over both lists (moments about the first element), one workgroup reduction.
@@ -153,9 +177,6 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
     kde_on = okA && okR;
   }
 
-  const uint32_t seq = a.seq_id ? a.seq_id[b] : (uint32_t)b;
-  const uint32_t rnd = a.round ? a.round[b] : a.round0;
-
   // ---- half a wavefront per candidate position
   for (int i = grp; i < K; i += kGroups) {
     const size_t o = (size_t)b * K + i;
@@ -171,22 +192,31 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
       }
       continue;
     }
-    // everything the serial tail needs is requested now, so that it arrives behind the kernel sums
-    const int x = a.draft_tokens[o];
-    const bool x_ok = x >= 0 && x < a.map.V;
-    const char* prow = a.map.base[0] +
-        ((int64_t)b * a.map.seq_stride[0] + (int64_t)i * a.map.pos_stride[0]) * Elem<DT>::bytes;
-    const char* qrow = a.map.base[1] +
-        ((int64_t)b * a.map.seq_stride[1] + (int64_t)i * a.map.pos_stride[1]) * Elem<DT>::bytes;
-    const float zp = load_elem<DT>(prow, x_ok ? x : 0), zq = load_elem<DT>(qrow, x_ok ? x : 0);
-    const RowResult rp = ws.rows[2 * o], rq = ws.rows[2 * o + 1];
+    const PosLoad L = (i == grp) ? first : load_pos(i);
+    const RowResult& rp = L.rp;
+    const RowResult& rq = L.rq;
     const bool bad = rp.bad || rq.bad;
-    const double d = (double)a.d_js[o];
+    double d;
+    if (a.jsd_split > 0) {
+      // Two-kernel path: the JS kernel left one partial sum per slice.  The group adds them up in a
+      // fixed tree, corrects the common scale to first order (the weights were formed with the float
+      // roundings cp, cq of the normalisers, i.e. they are p(1+c), q(1+c') with c = ln2 (lse2_p - cp))
+      // and takes the root.
+      const double A = half_sum_d((double)L.p0 + (double)L.p1);
+      const double c0 = kLn2 * (rp.lse2 - (double)(float)rp.lse2), c1 = kLn2 * (rq.lse2 - (double)(float)rq.lse2);
+      double D = 0.5 * A * (1.0 - 0.5 * (c0 + c1));   // bits
+      D = fmin(fmax(D, 0.0), 1.0);
+      const float d_out = bad ? NAN : (float)sqrt(D);
+      if (l32 == 0) a.d_js[o] = d_out;
+      d = (double)d_out;
+    } else {
+      d = (double)a.d_js[o];
+    }
     double PA = 0.0;
     if (!bad && kde_on) {
       double ja = half_log_joint(d, LA, nA, kA);
       double jr = half_log_joint(d, LR, nR, kR);
-      PA = 1.0 / (1.0 + exp(jr - ja));
+      PA = 1.0 / (1.0 + (double)ex2((float)((jr - ja) * 1.44269504088896340736)));
     }
     if (l32 != 0) continue;
     sh.lse2[i][0] = rp.lse2;
@@ -202,21 +232,18 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
       atomicOr(&sh.status, (uint32_t)ADASD_ST_NONFINITE);
       continue;
     }
-    const U4 r = philox4x32_10(0u, (uint32_t)i, rnd, seq, a.seed_lo, a.seed_hi);
-    const double u1 = ((double)(r.w[0] >> 8) + 0.5) * (1.0 / 16777216.0);
-    const double u2 = ((double)(r.w[1] >> 8) + 0.5) * (1.0 / 16777216.0);
     // speculative-sampling test: accept with probability min(1, p(x)/q(x)), in the log domain
     int base = 0;
-    if (!x_ok) {
+    if (!L.x_ok) {
       atomicOr(&sh.status, (uint32_t)ADASD_ST_BAD_TOKEN);
     } else {
-      double lp = (double)zp - rp.lse2 * kLn2;
-      double lq = (double)zq - rq.lse2 * kLn2;
+      double lp = (double)L.zp - rp.lse2 * kLn2;
+      double lq = (double)L.zq - rq.lse2 * kLn2;
       double log_ratio = lp - lq;
       if (log_ratio > 0.0) log_ratio = 0.0;
-      base = log(u1) < log_ratio;   // false for NaN (both probabilities zero)
+      base = L.log_u1 < log_ratio;   // false for NaN (both probabilities zero)
     }
-    const int relaxed = a.reject_rule == 1 ? (PA >= 0.5) : (u2 < PA);
+    const int relaxed = a.reject_rule == 1 ? (PA >= 0.5) : (L.u2 < PA);
     if (a.p_accept) a.p_accept[o] = (float)PA;
     if (a.accept_mask) a.accept_mask[o] = (uint8_t)(base | (relaxed << 1));
     sh.acc[i] = (uint8_t)(base || relaxed);   // rejected only if both tests reject

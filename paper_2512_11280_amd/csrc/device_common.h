@@ -29,6 +29,15 @@ template <int BYTES> __device__ __forceinline__ void warm_kernargs() {
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }  // v_exp_f32
 __device__ __forceinline__ float lg2(float x) { return __builtin_amdgcn_logf(x); }   // v_log_f32
 
+// log2 of a positive finite float, as exponent + hardware log2 of the mantissa in [0.5, 1): absolute
+// error about 6e-8 whatever the magnitude.  A handful of instructions, where the double-precision
+// library routine is several hundred that a latency-bound kernel would have to fetch first.
+__device__ __forceinline__ double log2_acc(float x) {
+  int e;
+  const float m = __builtin_frexpf(x, &e);
+  return (double)e + (double)lg2(m);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Logit access.  A "vector" is 16 bytes: 8 bf16 or 4 fp32 logits.
 // ---------------------------------------------------------------------------------------------

@@ -29,13 +29,13 @@ struct RowMap {
 
 struct Workspace {
   float4* part1;      // [rows][kMaxSplit]   (m, s, u, -) partial log-sum-exp states
-  int32_t* ticket1;   // [rows]              arrival counters, zero between calls
+  int32_t* ticket1;   // [rows]              spare (zero)
   RowResult* rows;    // [rows]
   float2* part2;      // [positions][kMaxSplit] partial KL sums (p side, q side), log2 units
-  int32_t* ticket2;   // [positions]
+  int32_t* ticket2;   // [positions]         spare (zero)
   SamplePlan* plan;   // [B]
   Top2* part3;        // [B][kMaxSampleSplit]
-  int32_t* ticket3;   // [B]
+  int32_t* ticket3;   // [B]                 arrival counters of the sampling kernel, zero between calls
   int32_t* fused_cnt; // [positions][kCntStride] arrival counters of the fused kernel, one per 128-byte line
   uint64_t* fused_slots; // [positions][kMaxFusedSplit][kSlotWords] self-validating hand-off words, zero between calls
   uint64_t* fused_norm;  // [positions][kSlotWords] folded triples of both rows, published by the position's leader

@@ -1,11 +1,11 @@
 // Vocabulary-wide statistics: softmax normalisers + Shannon entropy of every row (Appendix A of
 // the paper) and the Jensen-Shannon distance of every (target, draft) row pair (Section 2.2).
 //
-// Two-kernel split-vocabulary form: each row is cut into S slices, one workgroup per slice;
-// partial results meet in the workspace and the workgroup that arrives last at a row's counter
-// folds them (fixed butterfly order, so results do not depend on arrival order).
-#include <cstdlib>
-
+// Two-kernel split-vocabulary form: each row is cut into S slices, one workgroup per slice.  The
+// first kernel leaves one (reference, sum, sum x*e) per row and slice in the workspace; every workgroup
+// of the second kernel folds the slices of its two rows itself (same code, same order, so the same
+// normalisers everywhere) and leaves one partial JS sum per position and slice, which the decision
+// kernel adds up in slice order.  Kernel boundaries are the only synchronisation.
 #include "internal.h"
 
 namespace adasd {
@@ -148,7 +148,7 @@ __device__ __forceinline__ RowResult fold_row(const Workspace& ws, int rho, int 
   const bool ok = (sw > 0.f) && (sw < INFINITY) && (fabsf(uw) < INFINITY) && (M > kNegHuge) && (M < INFINITY);
   RowResult res;
   if (ok) {
-    const double l2s = log2((double)sw);
+    const double l2s = log2_acc(sw);
     res.lse2 = (double)M + l2s;
     res.H = (float)(kLn2 * (l2s - (double)uw / (double)sw));
     res.bad = 0;
@@ -296,7 +296,6 @@ int pick_split(int rows, int V, int dt) {
   const int epv = dt == ADASD_BF16 ? 8 : 4;
   const int nv = V / epv;
   int S = (4096 + rows - 1) / (rows > 0 ? rows : 1);
-  if (const char* e = getenv("ADASD_SPLIT")) S = atoi(e);   // tuning experiments only
   int cap = nv / kBlock;            // at least one vector per thread and slice
   if (S > cap) S = cap;
   if (S > kMaxSplit) S = kMaxSplit;
