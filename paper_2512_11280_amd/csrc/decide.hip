@@ -15,41 +15,46 @@ __global__ void __launch_bounds__(kBlock) k_decide(DecideArgs a, Workspace ws) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Update step: one thread per sequence (at most k_max appends each).
+// Update step: one wavefront per sequence, one lane per candidate position (k_max <= 64).  Every lane
+// reads its position's distance at once; accepted positions that pass the open-interval filter are
+// appended in position order (rank = number of passing positions before it, from a ballot).
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(64) k_update(UpdateArgs a) {
   warm_kernargs<sizeof(UpdateArgs)>();
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= a.B) return;
+  const int b = blockIdx.x, lane = threadIdx.x;
   int kb = a.K;
   if (a.draft_len) kb = min(max(a.draft_len[b], 0), a.K);
   const int r = min(max(a.n_accept[b], 0), kb);
-  uint32_t st = 0;
-  float* LA = a.LA + (size_t)b * a.cap;
-  float* LR = a.LR + (size_t)b * a.cap;
-  int nA = a.nA[b], nR = a.nR[b];
+  const int nA = a.nA[b], nR = a.nR[b];
   const float lo = a.d_eps, hi = 1.0f - a.d_eps;
-  for (int i = 0; i < r; ++i) {
-    float d = a.d_js[(size_t)b * a.K + i];
-    if (d > lo && d < hi) {            // NaN fails both comparisons
-      if (nA < a.cap) LA[nA++] = d;
-      else st |= ADASD_ST_OVERFLOW;
-    }
+  float d = 0.f, H = 0.f;
+  if (lane <= r && lane < kb) d = a.d_js[(size_t)b * a.K + lane];
+  if (lane == r && r < kb) H = a.H_q[(size_t)b * a.K + r];
+  const bool pass = d > lo && d < hi;                       // NaN fails both comparisons
+  uint32_t st = 0;
+  // accepted positions 0 .. r-1
+  const unsigned long long acc = __ballot(pass && lane < r);
+  if (pass && lane < r) {
+    const int slot = nA + __popcll(acc & ((1ull << lane) - 1ull));
+    if (slot < a.cap) a.LA[(size_t)b * a.cap + slot] = d;
   }
+  const int nA_new = min(nA + __popcll(acc), a.cap);
+  if (nA + __popcll(acc) > a.cap) st |= ADASD_ST_OVERFLOW;
+  // the lane of the rejected position finishes the sequence (with all 64 positions accepted: the last lane)
+  if (lane != (r < 64 ? r : 63)) return;
+  int nR_new = nR;
   if (r < kb) {
-    float H = a.H_q[(size_t)b * a.K + r];
     if (isfinite(H)) {
       a.ent_sum[b] += (double)H;
       a.ent_cnt[b] += 1;
     }
-    float d = a.d_js[(size_t)b * a.K + r];
-    if (d > lo && d < hi) {
-      if (nR < a.cap) LR[nR++] = d;
+    if (pass) {
+      if (nR < a.cap) a.LR[(size_t)b * a.cap + nR_new++] = d;
       else st |= ADASD_ST_OVERFLOW;
     }
   }
-  a.nA[b] = nA;
-  a.nR[b] = nR;
+  a.nA[b] = nA_new;
+  a.nR[b] = nR_new;
   const int cnt = a.ent_cnt[b];
   a.T_G[b] = cnt > 0 ? (float)(a.ent_sum[b] / (double)cnt) : 0.f;
   if (a.status && st) a.status[b] |= st;
@@ -84,7 +89,7 @@ hipError_t launch_decide(const DecideArgs& a, const Workspace& ws, hipStream_t s
 
 hipError_t launch_update(const UpdateArgs& a, hipStream_t st) {
   if (a.B <= 0) return hipSuccess;
-  launch_kernel(k_update, dim3((a.B + 63) / 64), dim3(64), st, a);
+  launch_kernel(k_update, dim3(a.B), dim3(64), st, a);
   return hipGetLastError();
 }
 

@@ -317,15 +317,17 @@ def test_draft_entropy_rule(am, wl, oracle):
 
 
 # ------------------------------------------------------------------------------- update + closed loop
-def test_update_matches_oracle_and_state_round_trip(am, wl, oracle):
+@pytest.mark.parametrize("B,K,cap", [(9, 6, 12), (7, 64, 100)])   # 64: the largest window, every lane a position
+def test_update_matches_oracle_and_state_round_trip(am, wl, oracle, B, K, cap):
     from oracle import new_state
     rng = np.random.default_rng(31)
-    B, K, cap = 9, 6, 12
     host = new_state(B, cap)
     dev = am.State(B, cap)
     for rnd in range(8):
         dl = rng.integers(0, K + 1, B).astype(np.int32)
         na = np.minimum(rng.integers(0, K + 1, B), dl).astype(np.int32)
+        if rnd == 0:
+            dl[0], na[0] = K, K                 # whole window accepted
         Hq = rng.uniform(0.1, 6.0, (B, K)).astype(np.float32)
         dj = rng.uniform(0.0, 1.0, (B, K)).astype(np.float32)
         dj[0, 0], dj[1, 1], dj[2, 2] = 0.0, 1.0, 5e-7
