@@ -67,7 +67,7 @@ __device__ __forceinline__ void lse_push_vec(Lse& st, const uint4& q) {
 // Pass 1: partial (m, s, u) of one slice of one row.
 // ---------------------------------------------------------------------------------------------
 template <int DT, int kRowBatch>   // kRowBatch: vectors per thread and batch
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kBlock, 8)   // 64 registers: eight wavefronts per SIMD, 4096 workgroups in exactly two rounds
 k_rowstats(RowMap map, int S, Workspace ws) {
   warm_kernargs<sizeof(RowMap) + sizeof(int) + sizeof(Workspace)>();
   constexpr int EPV = Elem<DT>::per_vec;
