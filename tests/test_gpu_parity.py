@@ -118,6 +118,24 @@ def test_large_workload_full_size_sampled_sequences(am, wl, oracle):
     _report("large(B=128,k=16,V=152064), 8 sampled sequences", rep)
 
 
+def test_largest_window(am, wl, oracle, path):
+    """k_max = 64, the compiled limit: every decision group loops eight times, the update step uses
+    all 64 lanes."""
+    batch = wl.config_batched(B=3, k=64, V=2048, seed=64)
+    out, _, _ = G.run_gpu(am, batch, stats_path=path)
+    rep = G.compare_verify(out, G.run_oracle(oracle, batch))
+    _report("k=64", rep)
+
+
+def test_largest_vocabulary(am, wl, oracle):
+    """V = 2^24, the compiled limit, one position: 64 slices of 32768 vectors each, i.e. sixteen
+    batches per thread in both streaming kernels and 128 slices in the sampling kernel."""
+    batch = wl.config_batched(B=1, k=1, V=1 << 24, seed=24)
+    out, _, _ = G.run_gpu(am, batch)
+    rep = G.compare_verify(out, G.run_oracle(oracle, batch))
+    _report("V=2^24", rep)
+
+
 def test_ragged_lengths_sequence_ids_and_rounds(am, wl, oracle, path):
     batch = wl.config_batched(B=6, k=5, V=32003, seed=99)       # V not a multiple of 8: scalar tail
     batch.draft_len = torch.tensor([0, 1, 5, 3, 2, 5], dtype=torch.int32)
