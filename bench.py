@@ -3,8 +3,9 @@
 
 One step = one decode round's verification on the headline workload (B=32 sequences, k=8 drafted
 positions, V=128256, bf16 logits resident in HBM): adasd_verify (normalisers, entropies, JS distance,
-posterior, both acceptance tests, first reject, correction/bonus token) followed by
-adasd_update_thresholds.  Inputs rotate over several distinct seeded batches (> 512 MB in total) so
+posterior, both acceptance tests, first reject, correction/bonus token) with the update step of
+adasd_update_thresholds applied by the same call (options.apply_update; --separate-update makes it
+a second call).  Inputs rotate over several distinct seeded batches (> 512 MB in total) so
 that no cache carries logits from one step to the next.
 
 Prints ONE JSON line: throughput in verified positions/s, the HBM roofline fraction of the
@@ -38,6 +39,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sets", type=int, default=N_SETS)
     ap.add_argument("--stats-path", type=int, default=0, help="0 library default, 1 two-kernel path, 2 single-read kernel")
+    ap.add_argument("--separate-update", action="store_true",
+                    help="apply the update step with a separate adasd_update_thresholds call")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device-to-device copy of known size (counter calibration for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -68,7 +71,7 @@ def main():
     out = am.binding.alloc_verify_result(B, K)
     torch.cuda.synchronize()
 
-    opts = am.Options(stats_path=args.stats_path)
+    opts = am.Options(stats_path=args.stats_path, apply_update=0 if args.separate_update else 1)
     if args.calibrate_copy:
         src = sets[0][0]
         dst = torch.empty_like(src)
@@ -79,7 +82,8 @@ def main():
     def step(i):
         t, d, x, seed = sets[i % len(sets)]
         am.verify(t, d, x, ws, state=state, seed=seed, round0=i, options=opts, out=out)
-        am.update_thresholds(state, K, out.n_accept, out.H_q, out.d_js)
+        if args.separate_update:
+            am.update_thresholds(state, K, out.n_accept, out.H_q, out.d_js)
 
     for i in range(args.warmup):
         step(i)
@@ -170,7 +174,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"batched verify B={B} k={K} V={V} bf16 logits, "
                                f"{len(sets)} rotating seeded input sets, history lists 64+64 per sequence",
-                   "step": "adasd_verify + adasd_update_thresholds"},
+                   "step": "adasd_verify + adasd_update_thresholds" if args.separate_update
+                           else "adasd_verify with options.apply_update (update step in the decision kernel)"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": STAGE_TRAFFIC_BYTES if ("jsd" in kern_us and args.stats_path in (0, 1)) else None,

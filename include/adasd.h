@@ -106,6 +106,10 @@ typedef struct {
                           are read twice); 2 the single-read kernel when every row is 16-byte
                           aligned and V is a whole number of 16-byte vectors, else the two-kernel
                           path.  Same results to the documented tolerance either way. */
+  int32_t apply_update; /* 1: adasd_verify also applies the round to args->state, exactly as
+                          adasd_update_thresholds would with the same d_eps (the decision kernel
+                          does it after the sequence's decisions, which saves a launch);
+                          ADASD_ST_OVERFLOW is then OR-ed into the verify status.  Needs a state. */
 } adasd_options;
 
 /*
@@ -153,7 +157,8 @@ int adasd_draft_entropy(const void *draft_logits, adasd_dtype dt, int B, int V,
  *                                      u = ((word>>8) + 0.5) / 2^24;
  *   Gumbel noise of element v        : block v>>2, stream 1, word v&3, u = (word + 0.5) / 2^32.
  * Statistics are produced for every i < k_b (also after the first rejection); entries with
- * i >= k_b are set to 0.  The state is only read; apply the round with adasd_update_thresholds.
+ * i >= k_b are set to 0.  The state is only read unless options.apply_update is set; otherwise apply
+ * the round with adasd_update_thresholds.
  */
 typedef struct {
   /* inputs */

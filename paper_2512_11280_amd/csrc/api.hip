@@ -216,6 +216,8 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   if (opt.reject_rule != 0 && opt.reject_rule != 1) return ADASD_ERR_INVALID_ARG;
   if (opt.bw_rule != 0 && opt.bw_rule != 1) return ADASD_ERR_INVALID_ARG;
   if (opt.stats_path < 0 || opt.stats_path > 2) return ADASD_ERR_INVALID_ARG;
+  if (opt.apply_update != 0 && opt.apply_update != 1) return ADASD_ERR_INVALID_ARG;
+  if (opt.apply_update && !a->state) return ADASD_ERR_INVALID_ARG;
   if (a->B == 0) return ADASD_OK;
   const int B = a->B, K = a->k_max, V = a->V;
   if (!a->target_logits || !a->n_accept || !a->next_token || !a->status) return ADASD_ERR_INVALID_ARG;
@@ -300,9 +302,20 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
     }
     d.jsd_split = S;
   }
+  UpdateArgs upd{};            // B = 0: the state is only read
+  if (opt.apply_update) {
+    upd = state_args(a->state);
+    upd.K = K;
+    upd.n_accept = a->n_accept;
+    upd.draft_len = a->draft_len;
+    upd.H_q = a->H_q;
+    upd.d_js = a->d_js;
+    upd.d_eps = opt.d_eps > 0.f ? opt.d_eps : 1e-6f;
+    upd.status = a->status;
+  }
   {
     Scope sc(2, st);
-    if (launch_decide(d, ws, st) != hipSuccess) return ADASD_ERR_HIP;
+    if (launch_decide(d, upd, ws, st) != hipSuccess) return ADASD_ERR_HIP;
   }
 
   SampleArgs s{};

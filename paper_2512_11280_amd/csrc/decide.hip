@@ -8,10 +8,13 @@ namespace adasd {
 namespace {
 
 template <int DT>
-__global__ void __launch_bounds__(kBlock) k_decide(DecideArgs a, Workspace ws) {
-  warm_kernargs<sizeof(DecideArgs) + sizeof(Workspace)>();
+__global__ void __launch_bounds__(kBlock) k_decide(DecideArgs a, UpdateArgs upd, Workspace ws) {
+  warm_kernargs<sizeof(DecideArgs) + sizeof(UpdateArgs) + sizeof(Workspace)>();
   __shared__ DecideShared sh;
   decide_sequence<DT>(a, ws, blockIdx.x, sh);
+  // the round applied to the state right away (the lists were only read above, so the posteriors of
+  // this round used the history as it was)
+  if (upd.B > 0 && threadIdx.x < 64) update_sequence(upd, blockIdx.x, threadIdx.x, sh.first_reject, sh.k_b);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -21,43 +24,11 @@ __global__ void __launch_bounds__(kBlock) k_decide(DecideArgs a, Workspace ws) {
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(64) k_update(UpdateArgs a) {
   warm_kernargs<sizeof(UpdateArgs)>();
-  const int b = blockIdx.x, lane = threadIdx.x;
+  const int b = blockIdx.x;
   int kb = a.K;
   if (a.draft_len) kb = min(max(a.draft_len[b], 0), a.K);
   const int r = min(max(a.n_accept[b], 0), kb);
-  const int nA = a.nA[b], nR = a.nR[b];
-  const float lo = a.d_eps, hi = 1.0f - a.d_eps;
-  float d = 0.f, H = 0.f;
-  if (lane <= r && lane < kb) d = a.d_js[(size_t)b * a.K + lane];
-  if (lane == r && r < kb) H = a.H_q[(size_t)b * a.K + r];
-  const bool pass = d > lo && d < hi;                       // NaN fails both comparisons
-  uint32_t st = 0;
-  // accepted positions 0 .. r-1
-  const unsigned long long acc = __ballot(pass && lane < r);
-  if (pass && lane < r) {
-    const int slot = nA + __popcll(acc & ((1ull << lane) - 1ull));
-    if (slot < a.cap) a.LA[(size_t)b * a.cap + slot] = d;
-  }
-  const int nA_new = min(nA + __popcll(acc), a.cap);
-  if (nA + __popcll(acc) > a.cap) st |= ADASD_ST_OVERFLOW;
-  // the lane of the rejected position finishes the sequence (with all 64 positions accepted: the last lane)
-  if (lane != (r < 64 ? r : 63)) return;
-  int nR_new = nR;
-  if (r < kb) {
-    if (isfinite(H)) {
-      a.ent_sum[b] += (double)H;
-      a.ent_cnt[b] += 1;
-    }
-    if (pass) {
-      if (nR < a.cap) a.LR[(size_t)b * a.cap + nR_new++] = d;
-      else st |= ADASD_ST_OVERFLOW;
-    }
-  }
-  a.nA[b] = nA_new;
-  a.nR[b] = nR_new;
-  const int cnt = a.ent_cnt[b];
-  a.T_G[b] = cnt > 0 ? (float)(a.ent_sum[b] / (double)cnt) : 0.f;
-  if (a.status && st) a.status[b] |= st;
+  update_sequence(a, b, threadIdx.x, r, kb);
 }
 
 __global__ void __launch_bounds__(64) k_state_init(UpdateArgs a) {
@@ -78,12 +49,12 @@ __global__ void __launch_bounds__(256) k_zero(uint32_t* p, size_t n) {
 
 }  // namespace
 
-hipError_t launch_decide(const DecideArgs& a, const Workspace& ws, hipStream_t st) {
+hipError_t launch_decide(const DecideArgs& a, const UpdateArgs& upd, const Workspace& ws, hipStream_t st) {
   if (a.map.B <= 0) return hipSuccess;
   if (a.dt == ADASD_BF16)
-    launch_kernel(k_decide<ADASD_BF16>, dim3(a.map.B), dim3(kBlock), st, a, ws);
+    launch_kernel(k_decide<ADASD_BF16>, dim3(a.map.B), dim3(kBlock), st, a, upd, ws);
   else
-    launch_kernel(k_decide<ADASD_F32>, dim3(a.map.B), dim3(kBlock), st, a, ws);
+    launch_kernel(k_decide<ADASD_F32>, dim3(a.map.B), dim3(kBlock), st, a, upd, ws);
   return hipGetLastError();
 }
 

@@ -69,6 +69,7 @@ __device__ inline double half_log_joint(double d, const float* L, int n, const K
 }
 
 struct DecideShared {
+  int first_reject, k_b;            // of the sequence, for a fused update step
   double mom[kWaves][4];            // per-wave shifted moments of the two lists
   double lse2[ADASD_MAX_K][2];      // normalisers of the candidate positions (for the sampling plan)
   uint8_t acc[ADASD_MAX_K];         // 1: position accepted
@@ -249,32 +250,79 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
     sh.acc[i] = (uint8_t)(base || relaxed);   // rejected only if both tests reject
   }
   __syncthreads();
-  if (tid != 0) return;
-
-  int r = kb;
-  for (int i = 0; i < kb; ++i)
-    if (!sh.acc[i]) {
-      r = i;
-      break;
+  if (tid == 0) {
+    int r = kb;
+    for (int i = 0; i < kb; ++i)
+      if (!sh.acc[i]) {
+        r = i;
+        break;
+      }
+    a.n_accept[b] = r;
+    st |= sh.status;
+    SamplePlan plan;
+    plan.row = r;
+    plan.pad = 0;
+    if (r < kb) {
+      plan.residual = 1;
+      plan.valid = !sh.bad[r];
+      plan.lse2_p = sh.lse2[r][0];
+      plan.lse2_q = sh.lse2[r][1];
+    } else {
+      plan.residual = 0;   // bonus row: Gumbel-max needs no normaliser
+      plan.valid = 1;
+      plan.lse2_p = 0.0;
+      plan.lse2_q = 0.0;
     }
-  a.n_accept[b] = r;
-  st |= sh.status;
-  SamplePlan plan;
-  plan.row = r;
-  plan.pad = 0;
-  if (r < kb) {
-    plan.residual = 1;
-    plan.valid = !sh.bad[r];
-    plan.lse2_p = sh.lse2[r][0];
-    plan.lse2_q = sh.lse2[r][1];
-  } else {
-    plan.residual = 0;   // bonus row: Gumbel-max needs no normaliser
-    plan.valid = 1;
-    plan.lse2_p = 0.0;
-    plan.lse2_q = 0.0;
+    ws.plan[b] = plan;
+    a.status[b] = st;
+    sh.first_reject = r;
+    sh.k_b = kb;
   }
-  ws.plan[b] = plan;
-  a.status[b] = st;
+  __syncthreads();
+}
+
+}  // namespace adasd
+
+namespace adasd {
+
+// Update step of one sequence (Section 4.3, last paragraph of Section 4.4; update lines of Algorithm 1)
+// by one wavefront, one lane per candidate position (k_max <= 64).  Every lane reads its position's
+// distance at once; accepted positions that pass the open-interval filter are appended in position
+// order (rank = number of passing positions before it, from a ballot).
+__device__ inline void update_sequence(const UpdateArgs& a, int b, int lane, int r, int kb) {
+  const int nA = a.nA[b], nR = a.nR[b];
+  const float lo = a.d_eps, hi = 1.0f - a.d_eps;
+  float d = 0.f, H = 0.f;
+  if (lane <= r && lane < kb) d = a.d_js[(size_t)b * a.K + lane];
+  if (lane == r && r < kb) H = a.H_q[(size_t)b * a.K + r];
+  const bool pass = d > lo && d < hi;                       // NaN fails both comparisons
+  uint32_t st = 0;
+  // accepted positions 0 .. r-1
+  const unsigned long long acc = __ballot(pass && lane < r);
+  if (pass && lane < r) {
+    const int slot = nA + __popcll(acc & ((1ull << lane) - 1ull));
+    if (slot < a.cap) a.LA[(size_t)b * a.cap + slot] = d;
+  }
+  const int nA_new = min(nA + __popcll(acc), a.cap);
+  if (nA + __popcll(acc) > a.cap) st |= ADASD_ST_OVERFLOW;
+  // the lane of the rejected position finishes the sequence (with all 64 positions accepted: the last lane)
+  if (lane != (r < 64 ? r : 63)) return;
+  int nR_new = nR;
+  if (r < kb) {
+    if (isfinite(H)) {
+      a.ent_sum[b] += (double)H;
+      a.ent_cnt[b] += 1;
+    }
+    if (pass) {
+      if (nR < a.cap) a.LR[(size_t)b * a.cap + nR_new++] = d;
+      else st |= ADASD_ST_OVERFLOW;
+    }
+  }
+  a.nA[b] = nA_new;
+  a.nR[b] = nR_new;
+  const int cnt = a.ent_cnt[b];
+  a.T_G[b] = cnt > 0 ? (float)(a.ent_sum[b] / (double)cnt) : 0.f;
+  if (a.status && st) a.status[b] |= st;
 }
 
 }  // namespace adasd

@@ -83,6 +83,22 @@ bool fused_plan(const RowMap& map, int dt, int* NV_out, int* S_out);
 hipError_t launch_stats_fused(const RowMap& map, int dt, int NV, int S, int spin_limit,
                               const Workspace& ws, const VerifyOut& vout, hipStream_t st);
 
+struct UpdateArgs {
+  int32_t B, K, cap;
+  float* T_G;
+  double* ent_sum;
+  int32_t* ent_cnt;
+  float* LA;
+  float* LR;
+  int32_t* nA;
+  int32_t* nR;
+  const int32_t* n_accept;
+  const int32_t* draft_len;
+  const float* H_q;
+  const float* d_js;
+  float d_eps;
+  uint32_t* status;
+};
 struct DecideArgs {
   RowMap map;
   int32_t dt;
@@ -108,7 +124,8 @@ struct DecideArgs {
   uint8_t* accept_mask;
   uint32_t* status;
 };
-hipError_t launch_decide(const DecideArgs& a, const Workspace& ws, hipStream_t st);
+// upd.B > 0: the round is also applied to the state (the update step) by the same kernel
+hipError_t launch_decide(const DecideArgs& a, const UpdateArgs& upd, const Workspace& ws, hipStream_t st);
 // JS distance: per-slice partial sums (the decision kernel adds them up), rows and entropies
 hipError_t launch_jsd(const RowMap& map, int dt, int S, const Workspace& ws, const VerifyOut& vout,
                       hipStream_t st);
@@ -125,22 +142,6 @@ struct SampleArgs {
 };
 hipError_t launch_sample(const SampleArgs& a, int S, const Workspace& ws, hipStream_t st);
 
-struct UpdateArgs {
-  int32_t B, K, cap;
-  float* T_G;
-  double* ent_sum;
-  int32_t* ent_cnt;
-  float* LA;
-  float* LR;
-  int32_t* nA;
-  int32_t* nR;
-  const int32_t* n_accept;
-  const int32_t* draft_len;
-  const float* H_q;
-  const float* d_js;
-  float d_eps;
-  uint32_t* status;
-};
 hipError_t launch_update(const UpdateArgs& a, hipStream_t st);
 hipError_t launch_state_init(const UpdateArgs& a, hipStream_t st);
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);

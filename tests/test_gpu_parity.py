@@ -368,6 +368,28 @@ def test_update_matches_oracle_and_state_round_trip(am, wl, oracle, B, K, cap):
     assert (host["nA"] == cap).any()          # overflow was exercised
 
 
+def test_verify_with_fused_update_matches_verify_then_update(am, wl, oracle):
+    """options.apply_update: the decision kernel applies the round to the state; outputs and state must
+    equal those of adasd_verify followed by adasd_update_thresholds, and the oracle's."""
+    batch = wl.config_batched(B=6, k=7, V=8192, seed=77, cap=70)      # lists 64 long: some overflow at 70
+    batch.draft_len = torch.tensor([7, 0, 3, 7, 5, 1], dtype=torch.int32)
+    a, st_a, _ = G.run_gpu(am, batch)
+    am.update_thresholds(st_a, batch.k, a.n_accept, a.H_q, a.d_js, draft_len=batch.draft_len.cuda(), status=a.status)
+    b, st_b, _ = G.run_gpu(am, batch, options=am.Options(apply_update=1))
+    torch.cuda.synchronize()
+    for name in ("n_accept", "next_token", "H_p", "H_q", "d_js", "p_accept", "accept_mask", "status"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+    ha, hb = st_a.to_host(), st_b.to_host()
+    for k in ha:
+        assert np.array_equal(ha[k], hb[k]), k
+    ref = G.run_oracle(oracle, batch)
+    G.compare_verify(b, ref, info_bits=16 | 8)         # overflow bits come from the update step
+    host = {k: np.array(v, copy=True) for k, v in batch.state.items()}
+    oracle.update(host, ref["n_accept"], batch.draft_len.numpy(), ref["H_q"], ref["d_js"], batch.k, d_eps=1e-6)
+    for k in ("nA", "nR", "ent_cnt"):
+        assert np.array_equal(hb[k], host[k]), k
+
+
 def test_closed_loop_rounds_against_oracle(am, wl, oracle):
     """Draft-entropy stop rule -> verify -> update for several rounds; the oracle runs its own
     trajectory and the GPU is fed the oracle's state each round (never the other way round)."""
