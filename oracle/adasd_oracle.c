@@ -254,8 +254,20 @@ static void verify_one(const adasd_oracle_verify_args *a, int b, double *lp, dou
   const uint32_t rnd = a->round ? a->round[b] : a->round0;
   const float *LA = a->LA ? a->LA + (size_t)b * (size_t)a->cap : NULL;
   const float *LR = a->LR ? a->LR + (size_t)b * (size_t)a->cap : NULL;
-  const int nA = a->nA ? a->nA[b] : 0, nR = a->nR ? a->nR[b] : 0;
+  int nA = a->nA ? a->nA[b] : 0;
+  const int nR = a->nR ? a->nR[b] : 0;
   uint32_t st = 0;
+  /* Algorithm 1 appends to L_D^A inside the verification loop: work on a copy of the list that grows
+     as the loop goes (the state itself is still only changed by the update step, which repeats the
+     same appends).  A position is only reached in the paper's loop if every earlier one was accepted,
+     so "the distances of all earlier positions" is what it sees; positions after the first
+     rejection are reported under the same rule. */
+  float *work = NULL;
+  if (a->list_update == 1 && LA) {
+    work = (float *)malloc(sizeof(float) * (size_t)a->cap);
+    memcpy(work, LA, sizeof(float) * (size_t)a->cap);
+    LA = work;
+  }
 
   for (int i = 0; i < K; ++i) {
     size_t o = (size_t)b * (size_t)K + (size_t)i;
@@ -288,13 +300,17 @@ static void verify_one(const adasd_oracle_verify_args *a, int b, double *lp, dou
       adasd_oracle_accept_words(a->seed, seq, rnd, (uint32_t)i, &w1, &w2);
       double u1 = adasd_oracle_uniform24(w1), u2 = adasd_oracle_uniform24(w2);
 
-      /* speculative-sampling test: accept with probability min(1, p(x)/q(x)) */
       int base = 0;
       int32_t x = a->draft_tokens[o];
       if (x < 0 || x >= V) {
         st |= ADASD_ORACLE_ST_BAD_TOKEN;
         if (a->base_margin) a->base_margin[o] = INFINITY;
+      } else if (a->base_test == 1) {
+        /* Algorithm 1: y_i ~ p_i, accepted iff x_i = y_i, an event of probability p_i(x_i) */
+        base = log(u1) < lp[x];
+        if (a->base_margin) a->base_margin[o] = log(u1) - lp[x];
       } else {
+        /* speculative-sampling test: accept with probability min(1, p(x)/q(x)) */
         double log_ratio = lp[x] - lq[x];
         if (log_ratio > 0.0) log_ratio = 0.0;
         base = log(u1) < log_ratio; /* false when log_ratio is NaN (both probabilities zero) */
@@ -317,10 +333,13 @@ static void verify_one(const adasd_oracle_verify_args *a, int b, double *lp, dou
       /* a candidate is rejected only if BOTH tests reject it */
       accept = base || relaxed;
       a->accept_mask[o] = (uint8_t)(base | (relaxed << 1));
+      /* in-loop append of the accepted distance (open-interval filter, capacity as in the update step) */
+      if (work && dhat > a->d_eps && dhat < 1.0 - a->d_eps && nA < a->cap) work[nA++] = (float)dhat;
     }
     if (!accept && first_reject == k) first_reject = i;
   }
   a->n_accept[b] = first_reject;
+  free(work);
 
   /* token appended after the accepted prefix */
   const int r = first_reject;
@@ -332,7 +351,18 @@ static void verify_one(const adasd_oracle_verify_args *a, int b, double *lp, dou
     st |= ADASD_ORACLE_ST_NONFINITE;
   } else {
     int residual = 0;
-    if (r < k) {
+    int excluded = -1;
+    if (r < k && a->base_test == 1) {
+      /* y_r given y_r != x_r: the target distribution with the drafted token excluded */
+      int32_t x = a->draft_tokens[(size_t)b * (size_t)K + (size_t)r];
+      if (x >= 0 && x < V) {
+        double mass = 0.0;
+        for (int v = 0; v < V; ++v)
+          if (v != x) mass += exp(lp[v]);
+        if (mass > 0.0) excluded = x;
+        else st |= ADASD_ORACLE_ST_ZERO_MASS; /* all mass on x_r: fall back to the target distribution */
+      }
+    } else if (r < k) {
       const void *qrow = row_ptr(a->draft_logits, a->dtype,
                                  (int64_t)b * a->d_seq_stride + (int64_t)r * a->d_pos_stride);
       if (row_log_softmax(qrow, a->dtype, V, lq, NULL)) {
@@ -351,7 +381,7 @@ static void verify_one(const adasd_oracle_verify_args *a, int b, double *lp, dou
     /* Gumbel-max: argmax_v ln w_v - ln(-ln u_v); first index wins ties */
     for (int v = 0; v < V; ++v) {
       double w = residual ? exp(lp[v]) - exp(lq[v]) : exp(lp[v]);
-      if (!(w > 0.0)) continue;
+      if (v == excluded || !(w > 0.0)) continue;
       double u = adasd_oracle_uniform32(
           adasd_oracle_gumbel_word(a->seed, seq, rnd, (uint32_t)r, (uint32_t)v));
       double key = log(w) - log(-log(u));

@@ -109,6 +109,15 @@ typedef struct {
   int32_t kde_min_n;           /* >= 2 */
   int32_t bw_rule;             /* 0 Silverman, 1 Scott */
   int32_t relaxed_off;         /* 1: posterior test disabled */
+  int32_t base_test;           /* 0: speculative-sampling ratio test + residual resampling (Section 2.1.3);
+                                  1: the test of Algorithm 1's verification loop, x_i != y_i with
+                                     y_i ~ p_i, in its distribution-identical form: accept with
+                                     probability p_i(x_i); on rejection the appended token is y_r
+                                     given y_r != x_r, i.e. drawn from p_r with x_r excluded */
+  int32_t list_update;         /* 0: every position of the round sees the lists as of the round's start;
+                                  1: as in Algorithm 1's loop, position i sees the distances of
+                                     positions 1..i-1 of this round already appended to L_D^A */
+  double d_eps;                /* boundary band of the "0 < d < 1" filter used by list_update = 1 */
   /* outputs */
   int32_t *n_accept;           /* [B] */
   int32_t *next_token;         /* [B] */

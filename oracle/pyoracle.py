@@ -42,7 +42,8 @@ class _VerifyArgs(C.Structure):
         ("seed", C.c_uint64), ("seq_id", C.c_void_p), ("round", C.c_void_p),
         ("round0", C.c_uint32),
         ("reject_rule", C.c_int32), ("kde_min_n", C.c_int32), ("bw_rule", C.c_int32),
-        ("relaxed_off", C.c_int32),
+        ("relaxed_off", C.c_int32), ("base_test", C.c_int32), ("list_update", C.c_int32),
+        ("d_eps", C.c_double),
         ("n_accept", C.c_void_p), ("next_token", C.c_void_p),
         ("H_p", C.c_void_p), ("H_q", C.c_void_p), ("d_js", C.c_void_p),
         ("p_accept", C.c_void_p), ("accept_mask", C.c_void_p), ("status", C.c_void_p),
@@ -164,7 +165,7 @@ class Oracle:
     # -- verification -----------------------------------------------------
     def verify(self, target_logits, draft_logits, draft_tokens, draft_len=None, LA=None, LR=None,
                nA=None, nR=None, seed=0, seq_id=None, rounds=None, round0=0, reject_rule=0,
-               kde_min_n=2, bw_rule=0, relaxed_off=0):
+               kde_min_n=2, bw_rule=0, relaxed_off=0, base_test=0, list_update=0, d_eps=1e-6):
         t, dt = _as_logit_array(target_logits)
         d, dt2 = _as_logit_array(draft_logits)
         assert dt == dt2
@@ -193,7 +194,7 @@ class Oracle:
         a = _VerifyArgs(
             _ptr(t), _ptr(d), dt, B, K, V, K1 * V, V, K * V, V, _ptr(tok), _ptr(dl), cap,
             _ptr(LA), _ptr(LR), _ptr(nA), _ptr(nR), seed, _ptr(sid), _ptr(rnd), round0,
-            reject_rule, kde_min_n, bw_rule, relaxed_off,
+            reject_rule, kde_min_n, bw_rule, relaxed_off, base_test, list_update, d_eps,
             _ptr(out["n_accept"]), _ptr(out["next_token"]), _ptr(out["H_p"]), _ptr(out["H_q"]),
             _ptr(out["d_js"]), _ptr(out["p_accept"]), _ptr(out["accept_mask"]),
             _ptr(out["status"]), _ptr(out["base_margin"]), _ptr(out["relaxed_margin"]),
