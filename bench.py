@@ -41,6 +41,9 @@ def main():
     ap.add_argument("--stats-path", type=int, default=0, help="0 library default, 1 two-kernel path, 2 single-read kernel")
     ap.add_argument("--separate-update", action="store_true",
                     help="apply the update step with a separate adasd_update_thresholds call")
+    ap.add_argument("--literal", action="store_true",
+                    help="time the variant that follows Algorithm 1's loop as written (options base_test=1, "
+                         "list_update=1) instead of the default readings")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device-to-device copy of known size (counter calibration for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -71,7 +74,8 @@ def main():
     out = am.binding.alloc_verify_result(B, K)
     torch.cuda.synchronize()
 
-    opts = am.Options(stats_path=args.stats_path, apply_update=0 if args.separate_update else 1)
+    opts = am.Options(stats_path=args.stats_path, apply_update=0 if args.separate_update else 1,
+                      base_test=1 if args.literal else 0, list_update=1 if args.literal else 0)
     if args.calibrate_copy:
         src = sets[0][0]
         dst = torch.empty_like(src)
@@ -152,7 +156,8 @@ def main():
         c0 = time.perf_counter()
         for r in range(reps):
             ora.verify(host0.target, host0.draft, host0.draft_tokens.numpy(), LA=s["LA"], LR=s["LR"],
-                       nA=s["nA"], nR=s["nR"], seed=host0.seed, round0=r)
+                       nA=s["nA"], nR=s["nR"], seed=host0.seed, round0=r,
+                       base_test=opts.base_test, list_update=opts.list_update)
         c1 = time.perf_counter()
         cpu = {"value": B * K * reps / (c1 - c0), "unit": "verified positions/s",
                "cores": ora.num_threads(), "kind": "oracle",
@@ -175,7 +180,9 @@ def main():
         "config": {"workload": f"batched verify B={B} k={K} V={V} bf16 logits, "
                                f"{len(sets)} rotating seeded input sets, history lists 64+64 per sequence",
                    "step": "adasd_verify + adasd_update_thresholds" if args.separate_update
-                           else "adasd_verify with options.apply_update (update step in the decision kernel)"},
+                           else "adasd_verify with options.apply_update (update step in the decision kernel)",
+                   "readings": "Algorithm 1's loop as written (base_test=1, list_update=1)" if args.literal
+                               else "defaults (ratio test + residual, lists as of the round's start)"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": STAGE_TRAFFIC_BYTES if ("jsd" in kern_us and args.stats_path in (0, 1)) else None,

@@ -90,7 +90,13 @@ typedef struct {
  */
 typedef struct {
   int32_t base_test;   /* 0: speculative-sampling ratio test min(1,p/q) with re-sampling from
-                          max(0,p-q) (Section 2.1.3).  Other values: ADASD_ERR_UNSUPPORTED. */
+                          max(0,p-q) (Section 2.1.3).
+                          1: the test written in Algorithm 1's verification loop, "x_i != y_i" with
+                          y_i drawn from p_i, in its distribution-identical form: the candidate
+                          passes with probability p_i(x_i) (u1 < p_i(x_i)); after a rejection the
+                          appended token is y_r given y_r != x_r, i.e. drawn from p_r with the drafted
+                          token excluded.  The draft logits then only enter H(q) and the JS distance.
+                          Other values: ADASD_ERR_INVALID_ARG. */
   int32_t reject_rule; /* the undefined Reject(P(A|d)) of Algorithm 1:
                           0: Bernoulli, candidate kept if u < P(A|d);  1: MAP, kept if P(A|d) >= 1/2 */
   int32_t kde_min_n;   /* the Bayesian test is off until both lists hold this many samples
@@ -110,6 +116,16 @@ typedef struct {
                           adasd_update_thresholds would with the same d_eps (the decision kernel
                           does it after the sequence's decisions, which saves a launch);
                           ADASD_ST_OVERFLOW is then OR-ed into the verify status.  Needs a state. */
+  int32_t list_update; /* when the accepted-distance list grows:
+                          0: after the round (every position of a round sees the lists as they were
+                          when the round started);
+                          1: inside the verification loop, as Algorithm 1 writes it: position i's
+                          posterior uses L_D^A extended by the distances of positions 1..i-1 of this
+                          round that pass the d_eps filter and fit the capacity (a position is only
+                          reached if all earlier ones were accepted; positions after the first
+                          rejection are reported under the same rule), with the list-size prior
+                          counted on the extended list.  The state itself is still only written by
+                          the update step, which leaves the same lists either way. */
 } adasd_options;
 
 /*

@@ -37,7 +37,7 @@ class _State(C.Structure):
 class _Options(C.Structure):
     _fields_ = [("base_test", C.c_int32), ("reject_rule", C.c_int32), ("kde_min_n", C.c_int32),
                 ("bw_rule", C.c_int32), ("relaxed_off", C.c_int32), ("d_eps", C.c_float),
-                ("stats_path", C.c_int32), ("apply_update", C.c_int32)]
+                ("stats_path", C.c_int32), ("apply_update", C.c_int32), ("list_update", C.c_int32)]
 
 
 class _VerifyArgs(C.Structure):
@@ -125,10 +125,12 @@ class Options:
     d_eps: float = 1e-6
     stats_path: int = 0
     apply_update: int = 0
+    list_update: int = 0
 
     def _c(self) -> _Options:
         return _Options(self.base_test, self.reject_rule, self.kde_min_n, self.bw_rule,
-                        self.relaxed_off, self.d_eps, self.stats_path, self.apply_update)
+                        self.relaxed_off, self.d_eps, self.stats_path, self.apply_update,
+                        self.list_update)
 
 
 def workspace_bytes(B: int, k_max: int, V: int, dtype: torch.dtype) -> int:

@@ -212,7 +212,8 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   if (opt_in) opt = *opt_in;
   int rc = check_shape(a->B, a->k_max, a->V, (int)a->dt);
   if (rc) return rc;
-  if (opt.base_test != 0) return ADASD_ERR_UNSUPPORTED;
+  if (opt.base_test != 0 && opt.base_test != 1) return ADASD_ERR_INVALID_ARG;
+  if (opt.list_update != 0 && opt.list_update != 1) return ADASD_ERR_INVALID_ARG;
   if (opt.reject_rule != 0 && opt.reject_rule != 1) return ADASD_ERR_INVALID_ARG;
   if (opt.bw_rule != 0 && opt.bw_rule != 1) return ADASD_ERR_INVALID_ARG;
   if (opt.stats_path < 0 || opt.stats_path > 2) return ADASD_ERR_INVALID_ARG;
@@ -277,6 +278,9 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   d.kde_min_n = opt.kde_min_n;
   d.bw_rule = opt.bw_rule;
   d.relaxed_off = opt.relaxed_off;
+  d.base_test = opt.base_test;
+  d.list_update = opt.list_update;
+  d.d_eps = opt.d_eps > 0.f ? opt.d_eps : 1e-6f;
   d.n_accept = a->n_accept;
   d.H_p = a->H_p;
   d.H_q = a->H_q;
@@ -310,7 +314,7 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
     upd.draft_len = a->draft_len;
     upd.H_q = a->H_q;
     upd.d_js = a->d_js;
-    upd.d_eps = opt.d_eps > 0.f ? opt.d_eps : 1e-6f;
+    upd.d_eps = d.d_eps;
     upd.status = a->status;
   }
   {

@@ -7,13 +7,12 @@ namespace adasd {
 
 namespace {
 
-template <int DT>
+template <int DT, bool INLOOP>
 __global__ void __launch_bounds__(kBlock) k_decide(DecideArgs a, UpdateArgs upd, Workspace ws) {
   warm_kernargs<sizeof(DecideArgs) + sizeof(UpdateArgs) + sizeof(Workspace)>();
   __shared__ DecideShared sh;
-  decide_sequence<DT>(a, ws, blockIdx.x, sh);
-  // the round applied to the state right away (the lists were only read above, so the posteriors of
-  // this round used the history as it was)
+  decide_sequence<DT, INLOOP>(a, ws, blockIdx.x, sh);
+  // the round applied to the state right away (the lists were only read above)
   if (upd.B > 0 && threadIdx.x < 64) update_sequence(upd, blockIdx.x, threadIdx.x, sh.first_reject, sh.k_b);
 }
 
@@ -51,10 +50,14 @@ __global__ void __launch_bounds__(256) k_zero(uint32_t* p, size_t n) {
 
 hipError_t launch_decide(const DecideArgs& a, const UpdateArgs& upd, const Workspace& ws, hipStream_t st) {
   if (a.map.B <= 0) return hipSuccess;
-  if (a.dt == ADASD_BF16)
-    launch_kernel(k_decide<ADASD_BF16>, dim3(a.map.B), dim3(kBlock), st, a, upd, ws);
-  else
-    launch_kernel(k_decide<ADASD_F32>, dim3(a.map.B), dim3(kBlock), st, a, upd, ws);
+  const dim3 grid(a.map.B), block(kBlock);
+  if (a.dt == ADASD_BF16) {
+    if (a.list_update) launch_kernel(k_decide<ADASD_BF16, true>, grid, block, st, a, upd, ws);
+    else launch_kernel(k_decide<ADASD_BF16, false>, grid, block, st, a, upd, ws);
+  } else {
+    if (a.list_update) launch_kernel(k_decide<ADASD_F32, true>, grid, block, st, a, upd, ws);
+    else launch_kernel(k_decide<ADASD_F32, false>, grid, block, st, a, upd, ws);
+  }
   return hipGetLastError();
 }
 

@@ -1,6 +1,5 @@
 // Device code of the acceptance decisions of one sequence (Section 2.1.3, Section 4.4 and the
-// verification loop of Algorithm 1 of the paper), shared by the stand-alone decision kernel and by
-// the JS-distance kernel, whose last workgroup of a sequence runs it in place.
+// verification loop of Algorithm 1 of the paper) and of the update step.
 #pragma once
 #include "internal.h"
 
@@ -68,17 +67,41 @@ __device__ inline double half_log_joint(double d, const float* L, int n, const K
   return tmax + kLn2 * log2_acc((float)total) - k.log_norm;
 }
 
+// The same over a list that continues in a second array: samples 0..n-1 from L, n..n+nx-1 from X.
+__device__ inline double half_log_joint_ext(double d, const float* L, int n, const float* X, int nx, const Kde& k) {
+  const int l32 = threadIdx.x & 31, nt = n + nx;
+  double tmax = -INFINITY;
+  for (int j = l32; j < nt; j += 32) {
+    double e = d - (double)(j < n ? L[j] : X[j - n]);
+    tmax = fmax(tmax, -(e * e) * k.inv2h2);
+  }
+  tmax = half_max_d(tmax);
+  float acc = 0.f;
+  for (int j = l32; j < nt; j += 32) {
+    double e = d - (double)(j < n ? L[j] : X[j - n]);
+    double t = -(e * e) * k.inv2h2 - tmax;
+    acc += ex2((float)(t * 1.44269504088896340736));
+  }
+  const double total = half_sum_d((double)acc);
+  return tmax + kLn2 * log2_acc((float)total) - k.log_norm;
+}
+
 struct DecideShared {
   int first_reject, k_b;            // of the sequence, for a fused update step
+  float extra[ADASD_MAX_K];         // in-loop appends: this round's distances that pass the filter, in position order
+  uint8_t n_before[ADASD_MAX_K];    // in-loop appends: how many of them come from earlier positions
   double mom[kWaves][4];            // per-wave shifted moments of the two lists
   double lse2[ADASD_MAX_K][2];      // normalisers of the candidate positions (for the sampling plan)
   uint8_t acc[ADASD_MAX_K];         // 1: position accepted
   uint8_t bad[ADASD_MAX_K];
+  float dist[ADASD_MAX_K];          // in-loop appends: the round's distances
   uint32_t status;
 };
 
-// The decisions of one sequence by one workgroup of 256 threads.
-template <int DT>
+// The decisions of one sequence by one workgroup of 256 threads.  INLOOP: the accepted list grows
+// inside the verification loop (Algorithm 1): position i sees the list of the state followed by the
+// distances of positions 0..i-1 of this round that pass the open-interval filter, up to the capacity.
+template <int DT, bool INLOOP>
 __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b, DecideShared& sh) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = tid & 31, grp = tid >> 5;
   constexpr int kGroups = kBlock / 32;
@@ -134,6 +157,17 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
   PosLoad first;
   if (grp < kb) first = load_pos(grp);
 
+  // Two-kernel path: the JS kernel left one partial sum per slice.  The group adds them up in a fixed
+  // tree, corrects the common scale to first order (the weights were formed with the float roundings
+  // cp, cq of the normalisers, i.e. they are p(1+c), q(1+c') with c = ln2 (lse2_p - cp)) and takes the root.
+  auto fold_distance = [&](const PosLoad& L) {
+    const double A = half_sum_d((double)L.p0 + (double)L.p1);
+    const double c0 = kLn2 * (L.rp.lse2 - (double)(float)L.rp.lse2), c1 = kLn2 * (L.rq.lse2 - (double)(float)L.rq.lse2);
+    double D = 0.5 * A * (1.0 - 0.5 * (c0 + c1));   // bits
+    D = fmin(fmax(D, 0.0), 1.0);
+    return (L.rp.bad || L.rq.bad) ? NAN : (float)sqrt(D);
+  };
+
   // ---- Bayesian test set-up: both lists need enough samples and spread (else P(A|d) = 0).
   // One pass over both lists (moments about the first element), one workgroup reduction.
   const int min_n = a.kde_min_n < 2 ? 2 : a.kde_min_n;
@@ -146,11 +180,40 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
     LA = a.LA + (size_t)b * a.cap;
     LR = a.LR + (size_t)b * a.cap;
   }
-  bool kde_on = !a.relaxed_off && nA >= min_n && nR >= min_n;
+  int n_room = 0;        // in-loop appends the list can still take
+  if (INLOOP) {
+    // All distances of the round first: the groups fold them, one wavefront ranks those that pass.
+    for (int i = grp; i < kb; i += kGroups) {
+      const size_t o = (size_t)b * K + i;
+      const PosLoad L = (i == grp) ? first : load_pos(i);
+      float dv;
+      if (a.jsd_split > 0) {
+        dv = fold_distance(L);
+        if (l32 == 0) a.d_js[o] = dv;
+      } else {
+        dv = (L.rp.bad || L.rq.bad) ? NAN : a.d_js[o];
+      }
+      if (l32 == 0) sh.dist[i] = dv;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      const float dv = lane < kb ? sh.dist[lane] : NAN;
+      const bool pass = dv > a.d_eps && dv < 1.0f - a.d_eps;      // NaN fails both
+      const unsigned long long mask = __ballot(pass);
+      const int rank = __popcll(mask & ((1ull << lane) - 1ull));
+      if (lane < kb) sh.n_before[lane] = (uint8_t)rank;
+      if (pass) sh.extra[rank] = dv;
+    }
+    __syncthreads();
+    n_room = LA ? max(a.cap - nA, 0) : 0;
+  }
+  bool kde_on = !a.relaxed_off && nR >= min_n && (INLOOP ? (LA != nullptr && nA + n_room >= min_n) : nA >= min_n);
   Kde kA, kR;
+  double cA = 0.0, cR = 0.0;
+  double m[4] = {0.0, 0.0, 0.0, 0.0};
   if (kde_on) {          // uniform over the workgroup
-    const double cA = (double)LA[0], cR = (double)LR[0];
-    double m[4] = {0.0, 0.0, 0.0, 0.0};
+    cA = nA > 0 ? (double)LA[0] : (double)sh.extra[0];   // (with an empty list the shift is only used once an extra exists)
+    cR = (double)LR[0];
     for (int j = tid; j < nA; j += kBlock) {
       const double e = (double)LA[j] - cA;
       m[0] += e;
@@ -173,9 +236,11 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
     __syncthreads();
 #pragma unroll
     for (int x = 0; x < 4; ++x) m[x] = (sh.mom[0][x] + sh.mom[1][x]) + (sh.mom[2][x] + sh.mom[3][x]);
-    const bool okA = kde_constants(m[0], m[1], nA, nR, a.bw_rule, &kA);
-    const bool okR = kde_constants(m[2], m[3], nR, nA, a.bw_rule, &kR);
-    kde_on = okA && okR;
+    if (!INLOOP) {
+      const bool okA = kde_constants(m[0], m[1], nA, nR, a.bw_rule, &kA);
+      const bool okR = kde_constants(m[2], m[3], nR, nA, a.bw_rule, &kR);
+      kde_on = okA && okR;
+    }
   }
 
   // ---- half a wavefront per candidate position
@@ -198,23 +263,34 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
     const RowResult& rq = L.rq;
     const bool bad = rp.bad || rq.bad;
     double d;
-    if (a.jsd_split > 0) {
-      // Two-kernel path: the JS kernel left one partial sum per slice.  The group adds them up in a
-      // fixed tree, corrects the common scale to first order (the weights were formed with the float
-      // roundings cp, cq of the normalisers, i.e. they are p(1+c), q(1+c') with c = ln2 (lse2_p - cp))
-      // and takes the root.
-      const double A = half_sum_d((double)L.p0 + (double)L.p1);
-      const double c0 = kLn2 * (rp.lse2 - (double)(float)rp.lse2), c1 = kLn2 * (rq.lse2 - (double)(float)rq.lse2);
-      double D = 0.5 * A * (1.0 - 0.5 * (c0 + c1));   // bits
-      D = fmin(fmax(D, 0.0), 1.0);
-      const float d_out = bad ? NAN : (float)sqrt(D);
+    if (INLOOP) {
+      d = (double)sh.dist[i];
+    } else if (a.jsd_split > 0) {
+      const float d_out = fold_distance(L);
       if (l32 == 0) a.d_js[o] = d_out;
       d = (double)d_out;
     } else {
       d = (double)a.d_js[o];
     }
     double PA = 0.0;
-    if (!bad && kde_on) {
+    if (INLOOP) {
+      if (!bad && kde_on) {
+        // the list as position i sees it: its size, its moments, the prior on the sizes
+        const int ne = min((int)sh.n_before[i], n_room), n_i = nA + ne;
+        double s1 = m[0], s2 = m[1];
+        for (int j = 0; j < ne; ++j) {
+          const double e = (double)sh.extra[j] - cA;
+          s1 += e;
+          s2 += e * e;
+        }
+        if (n_i >= min_n && kde_constants(s1, s2, n_i, nR, a.bw_rule, &kA) &&
+            kde_constants(m[2], m[3], nR, n_i, a.bw_rule, &kR)) {
+          double ja = half_log_joint_ext(d, LA, nA, sh.extra, ne, kA);
+          double jr = half_log_joint(d, LR, nR, kR);
+          PA = 1.0 / (1.0 + (double)ex2((float)((jr - ja) * 1.44269504088896340736)));
+        }
+      }
+    } else if (!bad && kde_on) {
       double ja = half_log_joint(d, LA, nA, kA);
       double jr = half_log_joint(d, LR, nR, kR);
       PA = 1.0 / (1.0 + (double)ex2((float)((jr - ja) * 1.44269504088896340736)));
@@ -233,10 +309,13 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
       atomicOr(&sh.status, (uint32_t)ADASD_ST_NONFINITE);
       continue;
     }
-    // speculative-sampling test: accept with probability min(1, p(x)/q(x)), in the log domain
+    // speculative-sampling test: accept with probability min(1, p(x)/q(x)), in the log domain; or the
+    // loop's own match test: accept with probability p(x)
     int base = 0;
     if (!L.x_ok) {
       atomicOr(&sh.status, (uint32_t)ADASD_ST_BAD_TOKEN);
+    } else if (a.base_test == 1) {
+      base = L.log_u1 < (double)L.zp - rp.lse2 * kLn2;
     } else {
       double lp = (double)L.zp - rp.lse2 * kLn2;
       double lq = (double)L.zq - rq.lse2 * kLn2;
@@ -261,9 +340,16 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
     st |= sh.status;
     SamplePlan plan;
     plan.row = r;
-    plan.pad = 0;
+    plan.excluded = -1;
     if (r < kb) {
       plan.residual = 1;
+      if (a.base_test == 1) {
+        // replacement from the target row without the drafted token (a broken token excludes nothing)
+        const int x = a.draft_tokens[(size_t)b * K + r];
+        const bool x_ok = x >= 0 && x < a.map.V;
+        plan.residual = x_ok ? 2 : 0;
+        plan.excluded = x_ok ? x : -1;
+      }
       plan.valid = !sh.bad[r];
       plan.lse2_p = sh.lse2[r][0];
       plan.lse2_q = sh.lse2[r][1];

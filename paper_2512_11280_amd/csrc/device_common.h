@@ -282,9 +282,9 @@ struct RowResult {   // one per logit row
 
 struct SamplePlan {  // one per sequence, written by the decision kernel
   int32_t row;       // position index r whose row(s) are sampled (k_b for the bonus row)
-  int32_t residual;  // 1: sample max(0, p_r - q_r); 0: sample p_row
+  int32_t residual;  // 1: sample max(0, p_r - q_r); 0: sample p_row; 2: sample p_row without token `excluded`
   int32_t valid;     // 0: the needed row is non-finite -> token -1
-  int32_t pad;
+  int32_t excluded;  // token index left out in mode 2, else -1
   double lse2_p, lse2_q;
 };
 

@@ -115,6 +115,9 @@ struct DecideArgs {
   const uint32_t* round;
   uint32_t round0;
   int32_t reject_rule, kde_min_n, bw_rule, relaxed_off;
+  int32_t base_test;    // 1: match test of the verification loop, replacement from p without the drafted token
+  int32_t list_update;  // 1: the accepted list grows inside the loop
+  float d_eps;          // filter of the in-loop appends
   // outputs
   int32_t* n_accept;
   float* H_p;

@@ -84,6 +84,11 @@ __device__ __forceinline__ float log2_exponential(uint32_t word) {
   return lg2(e);
 }
 
+// Sampling modes of a sequence (SamplePlan::residual)
+constexpr int kPlain = 0;      // the target row as it is (bonus row)
+constexpr int kResidual = 1;   // max(0, p - q)
+constexpr int kExclude = 2;    // the target row without one token (replacement after the loop's match test)
+
 // Upper-bound key of one vocabulary element.
 template <bool RESIDUAL>
 __device__ __forceinline__ float key_ub(float zp, float zq, float cp, float cq, uint32_t word) {
@@ -94,10 +99,11 @@ __device__ __forceinline__ float key_ub(float zp, float zq, float cp, float cq, 
   return lg2(w) - lE;
 }
 
-template <int DT, bool RESIDUAL>
+template <int DT, int MODE>
 __device__ __forceinline__ void scan_slice(const char* prow, const char* qrow, int V, int s, int S,
-                                           float cp, float cq, uint32_t c1, uint32_t c2, uint32_t c3,
+                                           float cp, float cq, int excluded, uint32_t c1, uint32_t c2, uint32_t c3,
                                            uint32_t k0, uint32_t k1, Top2& best, bool& poison) {
+  constexpr bool RESIDUAL = MODE == kResidual;
   constexpr int EPV = Elem<DT>::per_vec;
   const int tid = threadIdx.x;
   const bool fast = (reinterpret_cast<uintptr_t>(prow) & 15u) == 0 &&
@@ -130,9 +136,10 @@ __device__ __forceinline__ void scan_slice(const char* prow, const char* qrow, i
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float a = zp[4 * g + e];
-            if (!RESIDUAL) poison |= in && !(a < INFINITY);   // NaN or +inf in the bonus row
+            if (MODE == kPlain) poison |= in && !(a < INFINITY);   // NaN or +inf in the bonus row
             float k = key_ub<RESIDUAL>(a, RESIDUAL ? zq[4 * g + e] : 0.f, cp, cq, r.w[e]);
-            top2_push(best, in ? k : -INFINITY, base + 4 * g + e);
+            const bool use = MODE == kExclude ? (in && base + 4 * g + e != excluded) : in;
+            top2_push(best, use ? k : -INFINITY, base + 4 * g + e);
           }
         }
       }
@@ -150,9 +157,9 @@ __device__ __forceinline__ void scan_slice(const char* prow, const char* qrow, i
   for (int v = e0 + tid; v < e1; v += kBlock) {
     const U4 r = philox4x32_10((uint32_t)v >> 2, c1, c2, c3, k0, k1);
     const float a = load_elem<DT>(prow, v);
-    if (!RESIDUAL) poison |= !(a < INFINITY);
+    if (MODE == kPlain) poison |= !(a < INFINITY);
     float k = key_ub<RESIDUAL>(a, RESIDUAL ? load_elem<DT>(qrow, v) : 0.f, cp, cq, pick_word(r, v));
-    top2_push(best, k, v);
+    top2_push(best, (MODE == kExclude && v == excluded) ? -INFINITY : k, v);
   }
 }
 
@@ -192,7 +199,7 @@ __device__ double row_lse_exact(const char* row, int V, double* sh) {
 
 // Returns the token (all threads), -1 if the row has no finite logit.
 template <int DT>
-__device__ int sample_exact(const char* prow, const char* qrow, bool residual, int V, uint32_t c1,
+__device__ int sample_exact(const char* prow, const char* qrow, bool residual, int excluded, int V, uint32_t c1,
                             uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1, double* sh,
                             uint32_t* status_bits) {
   const double lse_p = row_lse_exact<DT>(prow, V, sh);
@@ -214,12 +221,22 @@ __device__ int sample_exact(const char* prow, const char* qrow, bool residual, i
       *status_bits |= ADASD_ST_ZERO_MASS;
     }
   }
+  if (excluded >= 0) {
+    double mass = 0.0;
+    for (int v = threadIdx.x; v < V; v += kBlock)
+      if (v != excluded) mass += exp((double)load_elem<DT>(prow, v) - lse_p);
+    mass = block_sum_d(mass, sh);
+    if (!(mass > 0.0)) {           // everything sits on the excluded token: the target row as it is
+      excluded = -1;
+      *status_bits |= ADASD_ST_ZERO_MASS;
+    }
+  }
   double best = -INFINITY;
   int tok = 0x7fffffff;
   for (int v = threadIdx.x; v < V; v += kBlock) {
     double w = exp((double)load_elem<DT>(prow, v) - lse_p);
     if (residual) w -= exp((double)load_elem<DT>(qrow, v) - lse_q);
-    if (!(w > 0.0)) continue;
+    if (v == excluded || !(w > 0.0)) continue;
     const U4 r = philox4x32_10((uint32_t)v >> 2, c1, c2, c3, k0, k1);
     const double u = ((double)pick_word(r, v) + 0.5) * (1.0 / 4294967296.0);
     const double key = log(w) - log(-log(u));
@@ -264,10 +281,12 @@ __global__ void __launch_bounds__(kBlock) k_sample(SampleArgs a, int S, Workspac
 
   Top2 best{-INFINITY, -1, -INFINITY, -1};
   bool poison = false;
-  if (plan.residual)
-    scan_slice<DT, true>(prow, qrow, V, s, S, cp, cq, c1, c2, c3, a.seed_lo, a.seed_hi, best, poison);
+  if (plan.residual == kResidual)
+    scan_slice<DT, kResidual>(prow, qrow, V, s, S, cp, cq, -1, c1, c2, c3, a.seed_lo, a.seed_hi, best, poison);
+  else if (plan.residual == kExclude)
+    scan_slice<DT, kExclude>(prow, qrow, V, s, S, cp, cq, plan.excluded, c1, c2, c3, a.seed_lo, a.seed_hi, best, poison);
   else
-    scan_slice<DT, false>(prow, qrow, V, s, S, cp, cq, c1, c2, c3, a.seed_lo, a.seed_hi, best, poison);
+    scan_slice<DT, kPlain>(prow, qrow, V, s, S, cp, cq, -1, c1, c2, c3, a.seed_lo, a.seed_hi, best, poison);
 
   __shared__ Top2 sh_top[kWaves];
   __shared__ int sh_flag[kWaves];
@@ -321,7 +340,7 @@ __global__ void __launch_bounds__(kBlock) k_sample(SampleArgs a, int S, Workspac
         mode = 2;   // nothing had (certain) mass
       } else {
         float margin = kGuard;
-        if (plan.residual) {
+        if (plan.residual == kResidual) {
           float p = ex2(fmaf(load_elem<DT>(prow, t.i1), kLog2e, -cp));
           float q = ex2(fmaf(load_elem<DT>(qrow, t.i1), kLog2e, -cq));
           float err = kErrRel * (p + q), w = p - q;
@@ -347,8 +366,9 @@ __global__ void __launch_bounds__(kBlock) k_sample(SampleArgs a, int S, Workspac
     return;
   }
   uint32_t bits = ADASD_ST_EXACT_PATH;
-  int tok = sample_exact<DT>(prow, qrow, plan.residual != 0, V, c1, c2, c3, a.seed_lo, a.seed_hi,
-                             sh_red, &bits);
+  int tok = sample_exact<DT>(prow, qrow, plan.residual == kResidual,
+                             plan.residual == kExclude ? plan.excluded : -1, V, c1, c2, c3, a.seed_lo,
+                             a.seed_hi, sh_red, &bits);
   if (tid == 0) {
     a.next_token[b] = tok;
     a.status[b] |= bits;

@@ -52,16 +52,27 @@ def run_oracle(oracle, batch, options=None, seq_id=None, rounds=None):
     kw = {}
     if options is not None:
         kw = dict(reject_rule=options.reject_rule, kde_min_n=options.kde_min_n,
-                  bw_rule=options.bw_rule, relaxed_off=options.relaxed_off)
+                  bw_rule=options.bw_rule, relaxed_off=options.relaxed_off,
+                  base_test=options.base_test, list_update=options.list_update,
+                  d_eps=float(np.float32(options.d_eps)) if options.d_eps > 0 else 1e-6)
     s = batch.state
     ref = oracle.verify(batch.target, batch.draft, batch.draft_tokens.numpy(),
                         draft_len=None if batch.draft_len is None else batch.draft_len.numpy(),
                         LA=s["LA"], LR=s["LR"], nA=s["nA"], nR=s["nR"], seed=batch.seed,
                         seq_id=seq_id, rounds=rounds, round0=batch.round0, **kw)
 
-    def posterior_at(b, d):
-        """The oracle's posterior of sequence b at a given distance (for the p_accept check)."""
-        return oracle.posterior(float(d), s["LA"][b, :int(s["nA"][b])], s["LR"][b, :int(s["nR"][b])],
+    def posterior_at(b, i, d):
+        """The oracle's posterior of sequence b, position i, at a given distance (for the p_accept
+        check).  With appends inside the loop the list is the state's followed by the oracle's own
+        distances of the earlier positions that pass the filter and fit the capacity."""
+        la = list(s["LA"][b, :int(s["nA"][b])])
+        if kw.get("list_update", 0):
+            eps, cap = kw["d_eps"], s["LA"].shape[1]
+            for j in range(i):
+                dj = ref["d_js"][b, j]
+                if eps < dj < 1.0 - eps and len(la) < cap:
+                    la.append(np.float32(dj))
+        return oracle.posterior(float(d), np.float32(la), s["LR"][b, :int(s["nR"][b])],
                                 min_n=kw.get("kde_min_n", 2), bw_rule=kw.get("bw_rule", 0))
     ref["posterior_at"] = posterior_at
     return ref
@@ -93,7 +104,7 @@ def compare_verify(gpu, ref, info_bits=16):
     # fails, the posterior must still agree with the oracle's evaluated at the distance the GPU found.
     okp = close(g["p_accept"], ref["p_accept"], rtol=0.0, atol=PA_ATOL)
     for b, i in np.argwhere(~okp):
-        at_gpu_d = ref["posterior_at"](b, g["d_js"][b, i])
+        at_gpu_d = ref["posterior_at"](b, i, g["d_js"][b, i])
         assert abs(g["p_accept"][b, i] - at_gpu_d) <= PA_ATOL, \
             f"p_accept mismatch at {(b, i)}: gpu {g['p_accept'][b, i]!r}, oracle at the same distance " \
             f"{at_gpu_d!r}, oracle at its own distance {ref['p_accept'][b, i]!r}"

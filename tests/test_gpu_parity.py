@@ -213,6 +213,117 @@ def test_option_variants(am, wl, oracle, opt):
         assert (out.p_accept == 0).all()
 
 
+# ------------------------------------------------------------------------------- Algorithm 1 as written
+LITERAL = [dict(base_test=1), dict(list_update=1), dict(base_test=1, list_update=1),
+           dict(base_test=1, list_update=1, reject_rule=1), dict(list_update=1, bw_rule=1)]
+
+
+def _short_and_full_lists(batch, cap):
+    """History lists from empty to nearly full, so that a list becomes usable inside the round and
+    another one fills up inside it."""
+    st = batch.state
+    B = batch.B
+    nA = [0, 1, 2, cap - 2, cap, 64][:B] + [64] * max(B - 6, 0)
+    for b in range(B):
+        st["nA"][b] = nA[b]
+        if nA[b] > 64:
+            st["LA"][b, 64:nA[b]] = st["LA"][b, :nA[b] - 64]
+    return batch
+
+
+@pytest.mark.parametrize("opt", LITERAL, ids=lambda o: "+".join(f"{k}{v}" for k, v in o.items()))
+def test_literal_variant_of_the_verification_loop(am, wl, oracle, opt, path):
+    """The loop's own match test with the replacement drawn without the drafted token, and the accepted
+    list growing inside the loop."""
+    cap = 70
+    batch = _short_and_full_lists(wl.config_batched(B=7, k=6, V=32000, seed=23, cap=cap), cap)
+    options = am.Options(**opt)
+    out, _, _ = G.run_gpu(am, batch, options=options, stats_path=path)
+    ref = G.run_oracle(oracle, batch, options=options)
+    rep = G.compare_verify(out, ref)
+    _report(f"literal {opt}", rep)
+    pa = ref["p_accept"]
+    if opt.get("list_update"):
+        assert pa[0, 0] == 0 and pa[0, 1] == 0 and pa[0, 2:].max() > 0      # empty list: usable from the third position
+        assert pa[1, 0] == 0 and pa[1, 1:].max() > 0
+        flat = G.run_oracle(oracle, batch, options=am.Options(**{**opt, "list_update": 0}))
+        assert not np.allclose(flat["p_accept"], pa, rtol=1e-3, atol=1e-6)
+    if opt.get("base_test"):
+        rej = ref["n_accept"] < batch.k
+        tok = batch.draft_tokens.numpy()
+        nt = out.next_token.cpu().numpy()
+        assert rej.any()
+        assert all(nt[b] != tok[b, ref["n_accept"][b]] for b in np.flatnonzero(rej))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("V", [8, 100, 1001, 20011])
+def test_literal_variant_small_and_ragged_vocabularies(am, wl, oracle, dtype, V):
+    batch = wl.config_batched(B=5, k=5, V=V, seed=100 + V, dtype=dtype, cap=80)
+    batch.draft_len = torch.tensor([5, 0, 3, 5, 1], dtype=torch.int32)
+    options = am.Options(base_test=1, list_update=1)
+    out, _, _ = G.run_gpu(am, batch, options=options)
+    rep = G.compare_verify(out, G.run_oracle(oracle, batch, options=options))
+    _report(f"literal V={V} {dtype}", rep)
+
+
+def test_literal_variant_largest_window_and_unaligned_rows(am, wl, oracle):
+    # 64 positions, a list with room for 10 more samples: the in-loop appends stop at the capacity
+    batch = wl.config_batched(B=2, k=64, V=4099, seed=5, cap=74)
+    options = am.Options(base_test=1, list_update=1)
+    out, _, _ = G.run_gpu(am, batch, options=options)
+    ref = G.run_oracle(oracle, batch, options=options)
+    rep = G.compare_verify(out, ref)
+    _report("literal K=64", rep)
+    assert (ref["p_accept"][:, 11:] > 0).any()
+
+
+def test_literal_variant_with_the_update_in_the_same_call(am, wl, oracle):
+    """The state after the round does not depend on when the posteriors saw the appends."""
+    batch = wl.config_batched(B=6, k=7, V=8192, seed=78, cap=70)
+    batch.draft_len = torch.tensor([7, 0, 3, 7, 5, 1], dtype=torch.int32)
+    options = am.Options(base_test=1, list_update=1, apply_update=1)
+    out, st, _ = G.run_gpu(am, batch, options=options)
+    ref = G.run_oracle(oracle, batch, options=options)
+    rep = G.compare_verify(out, ref, info_bits=16 | 8)
+    host = {k: np.array(v, copy=True) for k, v in batch.state.items()}
+    oracle.update(host, ref["n_accept"], batch.draft_len.numpy(), ref["H_q"], ref["d_js"], batch.k, d_eps=1e-6)
+    got = st.to_host()
+    if rep["flips"] == 0:
+        for k in ("nA", "nR", "ent_cnt"):
+            assert np.array_equal(got[k], host[k]), k
+
+
+def test_literal_variant_status_and_float64_path(am, wl, oracle):
+    """Broken draft token at the rejected position (nothing to exclude), and replacement draws whose two
+    best keys nearly tie, found with the oracle: those take the float64 path, exclusion included."""
+    V = 256
+    g = torch.Generator().manual_seed(9)
+    n = 150000
+    t = (torch.randn(1, 2, V, generator=g) * 2).repeat(n, 1, 1).contiguous()
+    d = (torch.randn(1, 1, V, generator=g) * 2).repeat(n, 1, 1).contiguous()
+    tok = torch.full((n, 1), 3, dtype=torch.int32)
+    ref = oracle.verify(t.numpy(), d.numpy(), tok.numpy(), seed=31, relaxed_off=1, base_test=1)
+    rej = ref["n_accept"] == 0
+    close_call = np.flatnonzero(rej & (ref["top2_gap"] < 5e-5))[:6]
+    assert len(close_call) >= 2, "no near tie among the draws: widen the search"
+    ids = np.concatenate([close_call, np.flatnonzero(rej)[:2]]).astype(np.uint32)
+    B = len(ids)
+    tok_b = tok[:B].clone()
+    tok_b[-1, 0] = V + 7                                   # broken token: rejected, the row is sampled as it is
+    batch = wl.VerifyBatch(t[:B].contiguous(), d[:B].contiguous(), tok_b, None, wl.empty_state(B, 8), 31)
+    options = am.Options(base_test=1, relaxed_off=1)
+    out, _, _ = G.run_gpu(am, batch, options=options, seq_id=ids)
+    refb = G.run_oracle(oracle, batch, options=options, seq_id=ids)
+    rep = G.compare_verify(out, refb)
+    _report("literal exact path", rep)
+    assert np.array_equal(refb["next_token"][:len(close_call)], ref["next_token"][close_call])
+    st = out.status.cpu().numpy()
+    assert rep["exact_path"] >= 1
+    assert st[-1] & am.binding.ST_BAD_TOKEN and out.n_accept[-1].item() == 0
+    assert (out.next_token.cpu().numpy()[:-1] != 3).all()
+
+
 # ------------------------------------------------------------------------------- degenerate inputs
 def test_masked_identical_and_disjoint_rows(am, wl, oracle, path):
     V, K = 4100, 4
@@ -286,8 +397,11 @@ def test_argument_errors_are_reported_before_any_launch(am):
     d = torch.zeros(2, 2, 64, device="cuda")
     tok = torch.zeros(2, 2, dtype=torch.int32, device="cuda")
     with pytest.raises(am.AdasdError) as e:
-        am.verify(t, d, tok, ws, options=am.Options(base_test=1))
-    assert e.value.code == -3
+        am.verify(t, d, tok, ws, options=am.Options(base_test=2))
+    assert e.value.code == -1
+    with pytest.raises(am.AdasdError) as e:
+        am.verify(t, d, tok, ws, options=am.Options(list_update=3))
+    assert e.value.code == -1
     small = am.Workspace(1, 1, 64, torch.float32)
     with pytest.raises(am.AdasdError) as e:
         am.verify(t, d, tok, small)
@@ -390,9 +504,12 @@ def test_verify_with_fused_update_matches_verify_then_update(am, wl, oracle):
         assert np.array_equal(hb[k], host[k]), k
 
 
-def test_closed_loop_rounds_against_oracle(am, wl, oracle):
+@pytest.mark.parametrize("literal", [False, True], ids=["default", "literal"])
+def test_closed_loop_rounds_against_oracle(am, wl, oracle, literal):
     """Draft-entropy stop rule -> verify -> update for several rounds; the oracle runs its own
-    trajectory and the GPU is fed the oracle's state each round (never the other way round)."""
+    trajectory and the GPU is fed the oracle's state each round (never the other way round).
+    literal: the verification loop as Algorithm 1 writes it, from the empty lists on."""
+    options = am.Options(base_test=1, list_update=1) if literal else am.Options()
     from oracle import new_state
     B, V, W, cap, n_rounds = 4, 32000, 6, 256, 12
     src = wl.ClosedLoopSource(B, V, W, dtype=torch.bfloat16, seed=77)
@@ -429,9 +546,10 @@ def test_closed_loop_rounds_against_oracle(am, wl, oracle):
         dl_gpu = torch.tensor(dl_ref, device="cuda")
         lens.append(dl_ref.copy())
         batch = wl.VerifyBatch(t, d, x, torch.tensor(dl_ref), host, src.seed, rnd)
-        out = am.verify(t.cuda(), dg, x.cuda(), ws, state=dev, draft_len=dl_gpu, seed=src.seed, round0=rnd)
+        out = am.verify(t.cuda(), dg, x.cuda(), ws, state=dev, draft_len=dl_gpu, seed=src.seed, round0=rnd,
+                        options=options)
         torch.cuda.synchronize()
-        ref = G.run_oracle(oracle, batch)
+        ref = G.run_oracle(oracle, batch, options=options)
         rep = G.compare_verify(out, ref)
         total_flips += rep["flips"]
         am.update_thresholds(dev, W, out.n_accept, out.H_q, out.d_js, draft_len=dl_gpu)
