@@ -165,13 +165,21 @@ class Oracle:
     # -- verification -----------------------------------------------------
     def verify(self, target_logits, draft_logits, draft_tokens, draft_len=None, LA=None, LR=None,
                nA=None, nR=None, seed=0, seq_id=None, rounds=None, round0=0, reject_rule=0,
-               kde_min_n=2, bw_rule=0, relaxed_off=0, base_test=0, list_update=0, d_eps=1e-6):
+               kde_min_n=2, bw_rule=0, relaxed_off=0, base_test=0, list_update=0, d_eps=1e-6,
+               shared_rows=False):
+        """shared_rows: the logits hold ONE sequence ([1, k+1, V], [1, k, V]) that every row of
+        draft_tokens refers to (sequence stride 0): many draws on the same rows without copies."""
         t, dt = _as_logit_array(target_logits)
         d, dt2 = _as_logit_array(draft_logits)
         assert dt == dt2
         B, K1, V = t.shape
         K = K1 - 1
         assert d.shape == (B, K, V), (d.shape, t.shape)
+        seq = 1
+        if shared_rows:
+            assert B == 1
+            B = int(np.asarray(draft_tokens).shape[0])
+            seq = 0
         tok = np.ascontiguousarray(draft_tokens, dtype=np.int32).reshape(B, K)
         dl = None if draft_len is None else np.ascontiguousarray(draft_len, dtype=np.int32)
         cap = 0
@@ -192,7 +200,7 @@ class Oracle:
             base_margin=np.zeros((B, K), np.float64), relaxed_margin=np.zeros((B, K), np.float64),
             top2_gap=np.zeros(B, np.float64))
         a = _VerifyArgs(
-            _ptr(t), _ptr(d), dt, B, K, V, K1 * V, V, K * V, V, _ptr(tok), _ptr(dl), cap,
+            _ptr(t), _ptr(d), dt, B, K, V, seq * K1 * V, V, seq * K * V, V, _ptr(tok), _ptr(dl), cap,
             _ptr(LA), _ptr(LR), _ptr(nA), _ptr(nR), seed, _ptr(sid), _ptr(rnd), round0,
             reject_rule, kde_min_n, bw_rule, relaxed_off, base_test, list_update, d_eps,
             _ptr(out["n_accept"]), _ptr(out["next_token"]), _ptr(out["H_p"]), _ptr(out["H_q"]),

@@ -3,8 +3,11 @@
 // noise, argmax_v ln w_v - ln(-ln u_v), lowest index on ties.
 //
 // Fast path: float keys in the log2 domain that are UPPER BOUNDS of the true keys, running top-2 per
-// sequence.  The winner is final only if its lower bound beats the runner-up's upper bound;
-// otherwise the workgroup that arrives last re-does the sequence in float64 (exact path).
+// slice and sequence.  The winner is final only if its lower bound beats the runner-up's upper bound.
+// Otherwise the workgroup that arrives last settles the sequence in float64: first among the few
+// elements whose upper bound reaches the winner's lower bound (found from the per-slice records, a
+// slice with two such elements is scanned again), and only if that is still too close to call, or the
+// winner's mass is not certain, over the whole row (exact path).
 #include "internal.h"
 
 namespace adasd {
@@ -260,6 +263,165 @@ __device__ int sample_exact(const char* prow, const char* qrow, bool residual, i
   return t == 0x7fffffff ? -1 : t;
 }
 
+// Element ranges of slice s as scan_slice covers them: [a0, a1) and the row's unaligned tail [b0, b1).
+template <int DT>
+__device__ __forceinline__ void slice_ranges(bool fast, int V, int s, int S, int& a0, int& a1, int& b0, int& b1) {
+  constexpr int EPV = Elem<DT>::per_vec;
+  if (fast) {
+    const int nv = V / EPV, chunk = (nv + S - 1) / S, v0 = min(s * chunk, nv), v1 = min(v0 + chunk, nv);
+    a0 = v0 * EPV;
+    a1 = v1 * EPV;
+    b0 = nv * EPV;
+    b1 = (s == S - 1) ? V : b0;
+  } else {
+    a0 = (int)(((int64_t)s * V) / S);
+    a1 = (int)(((int64_t)(s + 1) * V) / S);
+    b0 = b1 = 0;
+  }
+}
+
+constexpr int kMaxCand = 64;      // elements that may still win
+constexpr int kMaxRescan = 8;     // slices that hold more than one of them
+
+struct RefineShared {
+  int n_cand, n_rescan;
+  int cand[kMaxCand];
+  int rescan[kMaxRescan];
+  double key[kMaxCand], err[kMaxCand];
+  int result;                     // token, or -1: too close, the whole row is needed
+};
+
+// Normaliser of a row to float64 accuracy in the arguments and one float ulp per term: sum of
+// 2^(z log2 e - c) around a first value c of the normaliser, each term the hardware exponential of the
+// float part of the argument times the first-order factor of the remainder.  Returns ln sum exp z.
+template <int DT>
+__device__ double row_lse_refined(const char* row, int V, double c_lse2, double* sh) {
+  constexpr int EPV = Elem<DT>::per_vec;
+  auto term = [&](float z) {
+    const double x = (double)z * 1.44269504088896340736 - c_lse2;
+    const float xf = (float)x;
+    return xf > -140.f ? (double)ex2(xf) * (1.0 + (x - (double)xf) * 0.69314718055994530942) : 0.0;
+  };
+  const int tid = threadIdx.x;
+  double acc = 0.0;
+  // one workgroup walks the whole row: several vectors per thread in flight, or the latency of each
+  // load is paid in full
+  const int nv = (reinterpret_cast<uintptr_t>(row) & 15u) == 0 ? V / EPV : 0;
+  const uint4* vp = reinterpret_cast<const uint4*>(row);
+  constexpr int NB = 4;
+  for (int base = 0; base < nv; base += NB * kBlock) {
+    uint4 x[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) x[j] = vp[min(base + tid + j * kBlock, nv - 1)];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      float z[EPV];
+      unpack<DT>(x[j], z);
+      double part = 0.0;
+#pragma unroll
+      for (int e = 0; e < EPV; ++e) part += term(z[e]);
+      if (base + tid + j * kBlock < nv) acc += part;
+    }
+  }
+  for (int v = nv * EPV + tid; v < V; v += kBlock) acc += term(load_elem<DT>(row, v));
+  acc = block_sum_d(acc, sh);
+  return (c_lse2 + log(acc) * 1.44269504088896340736) * 0.69314718055994530942;
+}
+
+// Settles a sequence among the elements whose upper-bound key is at least tau.  All threads of the
+// workgroup call it; returns the token, or -1 if the decision needs the whole row in float64.
+template <int DT>
+__device__ int sample_refine(const char* prow, const char* qrow, int mode, int excluded, int V, int b, int S,
+                             float tau, float cp, float cq, double lse2_p, double lse2_q, uint32_t c1,
+                             uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1, const Workspace& ws,
+                             double* sh_red, RefineShared& R) {
+  const int tid = threadIdx.x;
+  const bool residual = mode == kResidual;
+  if (tid == 0) R.n_cand = R.n_rescan = 0;
+  __syncthreads();
+  // per-slice records: the slice's best element if it reaches tau; the slice itself if its runner-up does
+  for (int j = tid; j < S; j += kBlock) {
+    const Top2* src = &ws.part3[(size_t)b * kMaxSampleSplit + j];
+    const float s_k1 = ld_agent(&src->k1), s_k2 = ld_agent(&src->k2);
+    const int s_i1 = ld_agent(&src->i1);
+    if (s_k2 >= tau) {
+      const int at = atomicAdd(&R.n_rescan, 1);
+      if (at < kMaxRescan) R.rescan[at] = j;
+    } else if (s_k1 >= tau && s_i1 >= 0) {
+      const int at = atomicAdd(&R.n_cand, 1);
+      if (at < kMaxCand) R.cand[at] = s_i1;
+    }
+  }
+  __syncthreads();
+  const int n_rescan = R.n_rescan;
+  if (n_rescan > kMaxRescan) return -1;
+  const bool fast = (reinterpret_cast<uintptr_t>(prow) & 15u) == 0 &&
+                    (!residual || (reinterpret_cast<uintptr_t>(qrow) & 15u) == 0);
+  for (int n = 0; n < n_rescan; ++n) {
+    int lo[2], hi[2];
+    slice_ranges<DT>(fast, V, R.rescan[n], S, lo[0], hi[0], lo[1], hi[1]);
+    for (int part = 0; part < 2; ++part)
+      for (int v = lo[part] + tid; v < hi[part]; v += kBlock) {
+        const U4 r = philox4x32_10((uint32_t)v >> 2, c1, c2, c3, k0, k1);
+        const float zp = load_elem<DT>(prow, v);
+        const float k = residual ? key_ub<true>(zp, load_elem<DT>(qrow, v), cp, cq, pick_word(r, v))
+                                 : key_ub<false>(zp, 0.f, cp, cq, pick_word(r, v));
+        if (k >= tau && v != excluded) {
+          const int at = atomicAdd(&R.n_cand, 1);
+          if (at < kMaxCand) R.cand[at] = v;
+        }
+      }
+  }
+  __syncthreads();
+  const int n_cand = R.n_cand;
+  if (n_cand > kMaxCand || n_cand == 0) return -1;
+  // float64 keys of the candidates.  Without a draft row the normaliser is a common shift and drops
+  // out; with it both normalisers are refined first (workgroup-wide), and each key carries the bound
+  // 2^-21 (p + q) / w of what their remaining error can do to ln w.
+  double lse_p = 0.0, lse_q = 0.0;
+  if (residual) {
+    lse_p = row_lse_refined<DT>(prow, V, lse2_p, sh_red);
+    lse_q = row_lse_refined<DT>(qrow, V, lse2_q, sh_red);
+  }
+  if (tid < n_cand) {
+    const int v = R.cand[tid];
+    const U4 r = philox4x32_10((uint32_t)v >> 2, c1, c2, c3, k0, k1);
+    const double u = ((double)pick_word(r, v) + 0.5) * (1.0 / 4294967296.0);
+    const double g = log(-log(u));
+    double key, err = 0.0;
+    if (residual) {
+      const double p = exp((double)load_elem<DT>(prow, v) - lse_p), q = exp((double)load_elem<DT>(qrow, v) - lse_q);
+      const double w = p - q;
+      err = w > 0.0 ? 0x1p-21 * (p + q) / w : INFINITY;
+      key = w > 0.0 ? log(w) - g : -INFINITY;
+    } else {
+      key = (double)load_elem<DT>(prow, v) - g;
+    }
+    R.key[tid] = key;
+    R.err[tid] = err;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int best = 0;
+    for (int c = 1; c < n_cand; ++c)
+      if (R.key[c] > R.key[best] || (R.key[c] == R.key[best] && R.cand[c] < R.cand[best])) best = c;
+    int result = R.cand[best];
+    if (residual) {
+      // final only if no other candidate can overtake within the error bounds; a candidate whose mass
+      // is not certain at this accuracy sends the sequence to the whole-row path
+      if (!(R.err[best] < 0.25)) result = -1;
+      for (int c = 0; c < n_cand && result >= 0; ++c) {
+        if (c == best) continue;
+        if (!(R.err[c] < 0.25)) result = -1;
+        else if (!(R.key[best] - R.err[best] > R.key[c] + R.err[c])) result = -1;
+      }
+    }
+    R.result = result;
+  }
+  __syncthreads();
+  return R.result;
+}
+
 template <int DT>
 __global__ void __launch_bounds__(kBlock) k_sample(SampleArgs a, int S, Workspace ws) {
   warm_kernargs<sizeof(SampleArgs) + sizeof(int) + sizeof(Workspace)>();
@@ -319,6 +481,8 @@ __global__ void __launch_bounds__(kBlock) k_sample(SampleArgs a, int S, Workspac
   if (!sh_mode) return;
 
   // ---- last workgroup of this sequence: fold the S partial top-2 sets
+  // modes: 1 final; 2 settle among the close candidates; 3 broken bonus row; 4 whole row in float64
+  __shared__ float sh_tau;
   if (wave == 0) {
     Top2 t{-INFINITY, -1, -INFINITY, -1};
     int flag = 0;
@@ -337,7 +501,7 @@ __global__ void __launch_bounds__(kBlock) k_sample(SampleArgs a, int S, Workspac
       if (flag) {
         mode = 3;   // NaN / +inf in the bonus row
       } else if (t.i1 < 0) {
-        mode = 2;   // nothing had (certain) mass
+        mode = 4;   // nothing had (certain) mass
       } else {
         float margin = kGuard;
         if (plan.residual == kResidual) {
@@ -345,10 +509,14 @@ __global__ void __launch_bounds__(kBlock) k_sample(SampleArgs a, int S, Workspac
           float q = ex2(fmaf(load_elem<DT>(qrow, t.i1), kLog2e, -cq));
           float err = kErrRel * (p + q), w = p - q;
           // true key >= key_ub - log2((w+err)/(w-err)); for err/w < 1/2 that is < 3 log2(e) err/w
-          if (!(w > 2.f * err)) mode = 2;
+          if (!(w > 2.f * err)) mode = 4;
           else margin += 3.f * kLog2e * err / w;
         }
-        if (!(t.k1 - t.k2 > margin)) mode = 2;
+        // an element whose upper bound stays below the winner's lower bound cannot be the true winner
+        if (mode == 1 && !(t.k1 - t.k2 > margin)) {
+          mode = 2;
+          sh_tau = t.k1 - margin;
+        }
       }
       if (mode == 1) a.next_token[b] = t.i1;
       sh_mode = mode;
@@ -356,7 +524,7 @@ __global__ void __launch_bounds__(kBlock) k_sample(SampleArgs a, int S, Workspac
     }
   }
   __syncthreads();
-  const int mode = sh_mode;
+  int mode = sh_mode;
   if (mode == 1) return;
   if (mode == 3) {
     if (tid == 0) {
@@ -366,9 +534,16 @@ __global__ void __launch_bounds__(kBlock) k_sample(SampleArgs a, int S, Workspac
     return;
   }
   uint32_t bits = ADASD_ST_EXACT_PATH;
-  int tok = sample_exact<DT>(prow, qrow, plan.residual == kResidual,
-                             plan.residual == kExclude ? plan.excluded : -1, V, c1, c2, c3, a.seed_lo,
-                             a.seed_hi, sh_red, &bits);
+  const int excluded = plan.residual == kExclude ? plan.excluded : -1;
+  int tok = -1;
+  if (mode == 2) {
+    __shared__ RefineShared sh_refine;
+    tok = sample_refine<DT>(prow, qrow, plan.residual, excluded, V, b, S, sh_tau, cp, cq, plan.lse2_p,
+                            plan.lse2_q, c1, c2, c3, a.seed_lo, a.seed_hi, ws, sh_red, sh_refine);
+  }
+  if (tok < 0)
+    tok = sample_exact<DT>(prow, qrow, plan.residual == kResidual, excluded, V, c1, c2, c3, a.seed_lo,
+                           a.seed_hi, sh_red, &bits);
   if (tid == 0) {
     a.next_token[b] = tok;
     a.status[b] |= bits;

@@ -324,6 +324,43 @@ def test_literal_variant_status_and_float64_path(am, wl, oracle):
     assert (out.next_token.cpu().numpy()[:-1] != 3).all()
 
 
+# ------------------------------------------------------------------------------- close calls of the argmax
+@pytest.mark.parametrize("dtype,V", [(torch.bfloat16, 4104), (torch.float32, 2056), (torch.bfloat16, 4107)],
+                         ids=["bf16-2slices", "f32-2slices", "bf16-unaligned"])
+@pytest.mark.parametrize("mode", ["residual", "bonus", "exclude"])
+def test_near_ties_of_the_gumbel_argmax_are_settled_in_float64(am, wl, oracle, mode, dtype, V):
+    """Draws whose two best keys lie closer than the float keys can tell apart, found with the oracle
+    among many draws on one pair of rows; the GPU must return the oracle's token for every one."""
+    g = torch.Generator().manual_seed(V)
+    t = (torch.randn(1, 2, V, generator=g) * 2.5).to(dtype)
+    d = (t[:, :1].float() + torch.randn(1, 1, V, generator=g)).to(dtype)
+    p = torch.softmax(t[0, 0].double(), -1)
+    q = torch.softmax(d[0, 0].double(), -1)
+    n = 100000
+    x = int(torch.argmax(q - p)) if mode == "residual" else int(torch.argmax(p - q))   # mostly rejected | always accepted
+    opt = dict(relaxed_off=1)
+    if mode == "exclude":
+        opt["base_test"] = 1
+        x = int(torch.argmin(p))
+    tok = np.full((n, 1), x, np.int32)
+    ref = oracle.verify(t, d, tok, seed=41, shared_rows=True, **opt)
+    want_reject = mode != "bonus"
+    sel = (ref["n_accept"] == (0 if want_reject else 1))
+    close_call = np.flatnonzero(sel & (ref["top2_gap"] < 1e-4))[:16]
+    assert len(close_call) >= 2, "no near tie among the draws: widen the search"
+    ids = close_call.astype(np.uint32)
+    B = len(ids)
+    batch = wl.VerifyBatch(t.repeat(B, 1, 1).contiguous(), d.repeat(B, 1, 1).contiguous(),
+                           torch.full((B, 1), x, dtype=torch.int32), None, wl.empty_state(B, 8), 41)
+    options = am.Options(**opt)
+    out, _, _ = G.run_gpu(am, batch, options=options, seq_id=ids)
+    refb = G.run_oracle(oracle, batch, options=options, seq_id=ids)
+    assert np.array_equal(refb["next_token"], ref["next_token"][close_call])
+    rep = G.compare_verify(out, refb)
+    _report(f"near ties {mode} V={V}", rep)
+    assert rep["flips"] == 0 and rep["exact_path"] >= 1       # too close for the float keys
+
+
 # ------------------------------------------------------------------------------- degenerate inputs
 def test_masked_identical_and_disjoint_rows(am, wl, oracle, path):
     V, K = 4100, 4
