@@ -418,6 +418,49 @@ int adasd_oracle_verify(const adasd_oracle_verify_args *a) {
 }
 
 /* ------------------------------------------------------------------------- */
+/* Drafting loop of Algorithm 1: x_i ~ q_i                                     */
+/* ------------------------------------------------------------------------- */
+void adasd_oracle_draft_sample(const void *logits, int dtype, int B, int V, int64_t row_stride,
+                               const uint8_t *active, int step, uint64_t seed,
+                               const uint32_t *seq_id, const uint32_t *round, uint32_t round0,
+                               int32_t *token_out, double *top2_gap) {
+#pragma omp parallel
+  {
+    double *lq = (double *)malloc(sizeof(double) * (size_t)V);
+#pragma omp for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+      token_out[b] = -1;
+      if (top2_gap) top2_gap[b] = 0.0;
+      if (active && !active[b]) continue;
+      if (row_log_softmax(row_ptr(logits, dtype, (int64_t)b * row_stride), dtype, V, lq, NULL)) continue;
+      const uint32_t seq = seq_id ? seq_id[b] : (uint32_t)b;
+      const uint32_t rnd = round ? round[b] : round0;
+      const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+      double best = -INFINITY, second = -INFINITY;
+      int token = -1;
+      for (int v = 0; v < V; ++v) {
+        if (!(exp(lq[v]) > 0.0)) continue;          /* no mass: never drawn */
+        const uint32_t ctr[4] = {(uint32_t)v >> 2, (uint32_t)step | (2u << 16), rnd, seq};
+        uint32_t out[4];
+        adasd_oracle_philox4x32_10(ctr, key, out);
+        const double u = adasd_oracle_uniform32(out[v & 3]);
+        const double k = lq[v] - log(-log(u));
+        if (k > best) {
+          second = best;
+          best = k;
+          token = v;
+        } else if (k > second) {
+          second = k;
+        }
+      }
+      token_out[b] = token;
+      if (top2_gap) top2_gap[b] = best - second;
+    }
+    free(lq);
+  }
+}
+
+/* ------------------------------------------------------------------------- */
 /* Update step of Algorithm 1                                                  */
 /* ------------------------------------------------------------------------- */
 static void list_append(float *L, int32_t *n, int cap, double d, uint32_t *st) {

@@ -87,6 +87,16 @@ void adasd_oracle_draft_entropy(const void *logits, int dtype, int B, int V,
                                 const uint8_t *active, int step, int k_max,
                                 double *H_out, uint8_t *stop_out);
 
+/* Generation loop of Algorithm 1, "x_i ~ q_i": one token per active row from softmax(row), by
+ * Gumbel-max, argmax_v ln q_v - ln(-ln u_v) with u_v the Philox word of counter
+ * (v>>2, step | 2<<16, round, sequence), word v&3 (a stream of its own: stream 1 belongs to the
+ * verification step's replacement draws); lowest index on ties.  token_out[b] = -1 for inactive rows
+ * and rows with NaN/+inf or without a finite logit.  top2_gap (may be NULL): best minus second key. */
+void adasd_oracle_draft_sample(const void *logits, int dtype, int B, int V, int64_t row_stride,
+                               const uint8_t *active, int step, uint64_t seed,
+                               const uint32_t *seq_id, const uint32_t *round, uint32_t round0,
+                               int32_t *token_out, double *top2_gap);
+
 typedef struct {
   /* inputs */
   const void *target_logits;  /* [B, k_max+1, V] */

@@ -98,6 +98,9 @@ class Oracle:
         L.adasd_oracle_draft_entropy.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int64,
                                                  C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                                  C.c_void_p, C.c_void_p]
+        L.adasd_oracle_draft_sample.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int64,
+                                                C.c_void_p, C.c_int, C.c_uint64, C.c_void_p, C.c_void_p,
+                                                C.c_uint32, C.c_void_p, C.c_void_p]
         L.adasd_oracle_verify.argtypes = [C.c_void_p]
         L.adasd_oracle_update.argtypes = [C.c_int, C.c_int, C.c_int] + [C.c_void_p] * 4 + \
             [C.c_double] + [C.c_void_p] * 8
@@ -161,6 +164,19 @@ class Oracle:
         self.L.adasd_oracle_draft_entropy(_ptr(z), dt, B, V, V, _ptr(tg), _ptr(act), step, k_max,
                                           _ptr(H), _ptr(stop))
         return H, stop
+
+    def draft_sample(self, logits, active=None, step=0, seed=0, seq_id=None, rounds=None, round0=0):
+        """x ~ softmax(row) for every active row; returns (tokens, top2_gap)."""
+        z, dt = _as_logit_array(logits)
+        B, V = z.shape
+        act = None if active is None else np.ascontiguousarray(active, dtype=np.uint8)
+        sid = None if seq_id is None else np.ascontiguousarray(seq_id, dtype=np.uint32)
+        rnd = None if rounds is None else np.ascontiguousarray(rounds, dtype=np.uint32)
+        tok = np.zeros(B, np.int32)
+        gap = np.zeros(B, np.float64)
+        self.L.adasd_oracle_draft_sample(_ptr(z), dt, B, V, V, _ptr(act), step, seed, _ptr(sid),
+                                         _ptr(rnd), round0, _ptr(tok), _ptr(gap))
+        return tok, gap
 
     # -- verification -----------------------------------------------------
     def verify(self, target_logits, draft_logits, draft_tokens, draft_len=None, LA=None, LR=None,
