@@ -145,6 +145,28 @@ def main():
                          H_out=H, stop_out=stop)
     torch.cuda.synchronize()
     draft_us = (time.perf_counter() - t1) / 200 * 1e6
+    # the same call with the token draw (x_i ~ q_i) in the same pass
+    tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    dst = torch.empty(B, dtype=torch.int32, device="cuda")
+    for _ in range(10):
+        am.draft_step(rows, ws, T_G=state.T_G, step=0, k_max=20, seed=1, H_out=H, stop_out=stop,
+                      token_out=tok, status_out=dst)
+    torch.cuda.synchronize()
+
+    def draft_steps():
+        for i in range(200):
+            am.draft_step(sets[i % len(sets)][1][:, i % K], ws, T_G=state.T_G, step=i % K, k_max=20, seed=1,
+                          round0=i, H_out=H, stop_out=stop, token_out=tok, status_out=dst)
+        torch.cuda.synchronize()
+
+    t1 = time.perf_counter()
+    draft_steps()
+    draft_step_us = (time.perf_counter() - t1) / 200 * 1e6
+    am.profile_enable(2 * 200 + 8)          # once more with the launches carrying events: kernel time only
+    draft_steps()
+    ms, n = am.profile_read(5)
+    draft_step_kernels_us = ms / 200 * 1e3 if n else None
+    am.profile_disable()
 
     # ---- CPU oracle on the same workload (baseline, not a target)
     cpu = None
@@ -193,6 +215,8 @@ def main():
         "cpu_baseline": cpu,
         "kernel_us": kern_us,
         "draft_entropy_us_per_call": draft_us,
+        "draft_step_us_per_call": draft_step_us,
+        "draft_step_kernels_us": draft_step_kernels_us,
         "mean_accepted_length": mean_accept,
     }
     print(json.dumps(line))

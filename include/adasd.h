@@ -155,6 +155,28 @@ int adasd_draft_entropy(const void *draft_logits, adasd_dtype dt, int B, int V,
                         size_t ws_bytes, void *stream);
 
 /*
+ * Draft side with the token draw (generation loop of Algorithm 1: "x_i ~ q_i", then the test
+ * H(q_i) > T_G; Section 4.3): everything adasd_draft_entropy returns, plus
+ *   token_out[b] = a token drawn from softmax(draft_logits[b, :]) by Gumbel-max,
+ *                  argmax_v z_v - ln(-ln u_v), lowest index on ties, in the same single pass over
+ *                  the logits (the normaliser does not move the argmax).  u_v is word v&3 of
+ *                  Philox4x32-10 with key `seed` and counter (v>>2, step | 2<<16, round, sequence),
+ *                  u = (w + 0.5) / 2^32: a stream of its own, disjoint from those of adasd_verify.
+ *                  sequence = seq_id[b] (b if NULL), round = round[b] (round0 if NULL).
+ *   status_out[b] (may be NULL) = ADASD_ST_NONFINITE for a row with NaN/+inf or no finite logit
+ *                  (token -1, H NaN, stop 1), ADASD_ST_EXACT_PATH if the draw was settled in
+ *                  float64, else 0.
+ * Inactive rows are not read and get H 0, stop 0, token -1.  Pointers are device memory owned by the
+ * caller; T_G, active, stop_out, seq_id, round, status_out may be NULL.  step must be below 65536.
+ * Errors as for adasd_draft_entropy; nothing is launched when one is returned.
+ */
+int adasd_draft_step(const void *draft_logits, adasd_dtype dt, int B, int V, int64_t row_stride,
+                     const float *T_G, const uint8_t *active, int step, int k_max, uint64_t seed,
+                     const uint32_t *seq_id, const uint32_t *round, uint32_t round0, float *H_out,
+                     uint8_t *stop_out, int32_t *token_out, uint32_t *status_out, void *workspace,
+                     size_t ws_bytes, void *stream);
+
+/*
  * Verification of one round (Sections 2.1.3, 2.2, 4.4; verification loop of Algorithm 1).
  * For sequence b with k_b = draft_len[b] candidates x_1..x_k (0-based position i below):
  *   p_i = softmax(target_logits[b,i,:]),  q_i = softmax(draft_logits[b,i,:]);

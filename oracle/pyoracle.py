@@ -165,16 +165,23 @@ class Oracle:
                                           _ptr(H), _ptr(stop))
         return H, stop
 
-    def draft_sample(self, logits, active=None, step=0, seed=0, seq_id=None, rounds=None, round0=0):
-        """x ~ softmax(row) for every active row; returns (tokens, top2_gap)."""
+    def draft_sample(self, logits, active=None, step=0, seed=0, seq_id=None, rounds=None, round0=0,
+                     shared_row=0):
+        """x ~ softmax(row) for every active row; returns (tokens, top2_gap).
+        shared_row = n > 0: logits hold ONE row [1, V] that n draws (sequences 0..n-1 unless seq_id is
+        given) refer to (row stride 0)."""
         z, dt = _as_logit_array(logits)
         B, V = z.shape
+        stride = V
+        if shared_row:
+            assert B == 1
+            B, stride = int(shared_row), 0
         act = None if active is None else np.ascontiguousarray(active, dtype=np.uint8)
         sid = None if seq_id is None else np.ascontiguousarray(seq_id, dtype=np.uint32)
         rnd = None if rounds is None else np.ascontiguousarray(rounds, dtype=np.uint32)
         tok = np.zeros(B, np.int32)
         gap = np.zeros(B, np.float64)
-        self.L.adasd_oracle_draft_sample(_ptr(z), dt, B, V, V, _ptr(act), step, seed, _ptr(sid),
+        self.L.adasd_oracle_draft_sample(_ptr(z), dt, B, V, stride, _ptr(act), step, seed, _ptr(sid),
                                          _ptr(rnd), round0, _ptr(tok), _ptr(gap))
         return tok, gap
 

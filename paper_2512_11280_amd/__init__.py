@@ -5,6 +5,6 @@ Every step runs in the HIP library ``libadasd.so`` (see ``include/adasd.h``); th
 marshals torch tensors into that C ABI.  There is no CPU fallback: calls raise if the library has
 not been built (``python -m paper_2512_11280_amd.build`` or ``__graft_entry__.build()``).
 """
-from .binding import (AdasdError, Options, State, VerifyResult, draft_entropy, library_path,  # noqa: F401
+from .binding import (AdasdError, Options, State, VerifyResult, draft_entropy, draft_step, library_path,  # noqa: F401
                       load_library, profile_disable, profile_enable, profile_read, set_spin_limit,
                       update_thresholds, verify, workspace_bytes, Workspace)

@@ -72,6 +72,10 @@ def load_library():
     L.adasd_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
     L.adasd_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
     L.adasd_state_init.argtypes = [C.POINTER(_State), C.c_void_p]
+    L.adasd_draft_step.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_void_p, C.c_void_p,
+                                   C.c_int, C.c_int, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint32,
+                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                   C.c_void_p]
     L.adasd_draft_entropy.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_void_p,
                                       C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_size_t, C.c_void_p]
@@ -202,6 +206,42 @@ def draft_entropy(draft_logits: torch.Tensor, workspace: Workspace, T_G: Optiona
         workspace.bytes, _stream())
     _check(rc, "adasd_draft_entropy")
     return H_out, stop_out
+
+
+def draft_step(draft_logits: torch.Tensor, workspace: Workspace, T_G: Optional[torch.Tensor] = None,
+               active: Optional[torch.Tensor] = None, step: int = 0, k_max: int = 1 << 30, seed: int = 0,
+               seq_id: Optional[torch.Tensor] = None, rounds: Optional[torch.Tensor] = None, round0: int = 0,
+               H_out: Optional[torch.Tensor] = None, stop_out: Optional[torch.Tensor] = None,
+               token_out: Optional[torch.Tensor] = None, status_out: Optional[torch.Tensor] = None):
+    """adasd_draft_step: H(q), the stop flag and a token drawn from softmax(row) for every row of
+    draft_logits [B, V].  Returns (H, stop, token, status)."""
+    if draft_logits.dim() != 2 or not draft_logits.is_cuda or draft_logits.stride(1) != 1:
+        raise ValueError("draft_logits must be a CUDA tensor [B, V] with contiguous vocabulary")
+    B, V = draft_logits.shape
+    dev = draft_logits.device
+    if H_out is None:
+        H_out = torch.empty(B, dtype=torch.float32, device=dev)
+    if stop_out is None:
+        stop_out = torch.empty(B, dtype=torch.uint8, device=dev)
+    if token_out is None:
+        token_out = torch.empty(B, dtype=torch.int32, device=dev)
+    if status_out is None:
+        status_out = torch.empty(B, dtype=torch.int32, device=dev)
+    _need(T_G, torch.float32, "T_G", optional=True)
+    _need(active, torch.uint8, "active", optional=True)
+    _need(seq_id, torch.int32, "seq_id", optional=True)
+    _need(rounds, torch.int32, "rounds", optional=True)
+    _need(H_out, torch.float32, "H_out")
+    _need(stop_out, torch.uint8, "stop_out")
+    _need(token_out, torch.int32, "token_out")
+    _need(status_out, torch.int32, "status_out")
+    rc = load_library().adasd_draft_step(
+        draft_logits.data_ptr(), _dtype_code(draft_logits), B, V, draft_logits.stride(0) if B > 1 else V,
+        _p(T_G), _p(active), step, k_max, seed & 0xFFFFFFFFFFFFFFFF, _p(seq_id), _p(rounds),
+        round0 & 0xFFFFFFFF, H_out.data_ptr(), stop_out.data_ptr(), token_out.data_ptr(),
+        status_out.data_ptr(), workspace.ptr, workspace.bytes, _stream())
+    _check(rc, "adasd_draft_step")
+    return H_out, stop_out, token_out, status_out
 
 
 @dataclass

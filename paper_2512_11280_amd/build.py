@@ -9,8 +9,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libadasd.so")
-SOURCES = ["stats.hip", "stats_fused.hip", "decide.hip", "sample.hip", "api.hip"]
-HEADERS = [os.path.join(CSRC, "device_common.h"), os.path.join(CSRC, "internal.h"),
+SOURCES = ["stats.hip", "stats_fused.hip", "decide.hip", "sample.hip", "draft.hip", "api.hip"]
+HEADERS = [os.path.join(CSRC, h) for h in ("device_common.h", "internal.h", "decide_device.h",
+                                             "sample_device.h", "stats_device.h")] + [
            os.path.join(os.path.dirname(HERE), "include", "adasd.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

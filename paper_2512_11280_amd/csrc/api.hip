@@ -201,9 +201,45 @@ int adasd_draft_entropy(const void* draft_logits, adasd_dtype dt, int B, int V, 
   map.V = V;
   DraftOut dout{T_G, H_out, stop_out, step + 1 >= k_max ? 1 : 0};
   hipStream_t st = (hipStream_t)stream;
-  const int S = pick_split(B, V, (int)dt);
+  const int S = pick_draft_split(B, V, (int)dt);
   Scope sc(5, st);
   return launch_rowstats(map, (int)dt, B, S, ws, &dout, st) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
+}
+
+int adasd_draft_step(const void* draft_logits, adasd_dtype dt, int B, int V, int64_t row_stride,
+                     const float* T_G, const uint8_t* active, int step, int k_max, uint64_t seed,
+                     const uint32_t* seq_id, const uint32_t* round, uint32_t round0, float* H_out,
+                     uint8_t* stop_out, int32_t* token_out, uint32_t* status_out, void* workspace,
+                     size_t ws_bytes, void* stream) {
+  int rc = check_shape(B, 0, V, (int)dt);
+  if (rc) return rc;
+  if (B == 0) return ADASD_OK;
+  if (!draft_logits || !H_out || !token_out || row_stride < V || step < 0 || step >= 65536 || k_max < 1)
+    return ADASD_ERR_INVALID_ARG;
+  const size_t es = dt == ADASD_BF16 ? 2 : 4;
+  if (!aligned_to(draft_logits, es) || !aligned_to(H_out, 4) || !aligned_to(T_G, 4) ||
+      !aligned_to(token_out, 4) || !aligned_to(status_out, 4) || !aligned_to(seq_id, 4) ||
+      !aligned_to(round, 4))
+    return ADASD_ERR_MISALIGNED;
+  if (!workspace) return ADASD_ERR_WORKSPACE;
+  if (!aligned_to(workspace, 256)) return ADASD_ERR_MISALIGNED;
+  Workspace ws;
+  if (workspace_layout(ws_bytes, &ws, workspace) < (size_t)B) return ADASD_ERR_WORKSPACE;
+
+  RowMap map{};
+  map.base[0] = static_cast<const char*>(draft_logits);
+  map.base[1] = nullptr;
+  map.seq_stride[0] = row_stride;
+  map.active = active;
+  map.K = 0;
+  map.B = B;
+  map.V = V;
+  DraftOut dout{T_G, H_out, stop_out, step + 1 >= k_max ? 1 : 0};
+  DraftDraw draw{(uint32_t)seed, (uint32_t)(seed >> 32), seq_id, round, round0, (uint32_t)step, token_out, status_out};
+  hipStream_t st = (hipStream_t)stream;
+  const int S = pick_draft_split(B, V, (int)dt);
+  Scope sc(5, st);
+  return launch_draft_step(map, (int)dt, S, ws, dout, draw, st) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
 }
 
 int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* stream) {

@@ -55,6 +55,20 @@ struct DraftOut {     // draft-entropy epilogue
   int32_t force_stop; // step + 1 >= k_max
 };
 
+struct DraftDraw {    // token draw of a drafting step (x_i ~ q_i)
+  uint32_t seed_lo, seed_hi;
+  const uint32_t* seq_id;
+  const uint32_t* round;
+  uint32_t round0;
+  uint32_t step;
+  int32_t* token_out;
+  uint32_t* status;   // may be null
+};
+// One drafting step: entropy, stop flag and drawn token of each row (two kernels: scan, finish)
+int pick_draft_split(int rows, int V, int dt);
+hipError_t launch_draft_step(const RowMap& map, int dt, int S, const Workspace& ws, const DraftOut& dout,
+                             const DraftDraw& draw, hipStream_t st);
+
 struct VerifyOut {
   float* H_p;
   float* H_q;

@@ -6,49 +6,11 @@
 // of the second kernel folds the slices of its two rows itself (same code, same order, so the same
 // normalisers everywhere) and leaves one partial JS sum per position and slice, which the decision
 // kernel adds up in slice order.  Kernel boundaries are the only synchronisation.
-#include "internal.h"
+#include "stats_device.h"
 
 namespace adasd {
 
 namespace {
-
-struct RowRef {
-  const char* ptr;
-  int b, i, which;
-  bool active;
-};
-
-template <int DT>
-__device__ __forceinline__ RowRef locate_row(const RowMap& map, int rho) {
-  RowRef r;
-  if (map.K > 0) {
-    r.which = rho & 1;
-    int pos = rho >> 1;
-    r.b = pos / map.K;
-    r.i = pos - r.b * map.K;
-    int kb = map.K;
-    if (map.draft_len) kb = min(max(map.draft_len[r.b], 0), map.K);
-    r.active = r.i < kb;
-  } else {
-    r.which = 0;
-    r.b = rho;
-    r.i = 0;
-    r.active = map.active ? (map.active[rho] != 0) : true;
-  }
-  int64_t off = (int64_t)r.b * map.seq_stride[r.which] + (int64_t)r.i * map.pos_stride[r.which];
-  r.ptr = map.base[r.which] + off * Elem<DT>::bytes;
-  return r;
-}
-
-__device__ __forceinline__ bool aligned16(const void* p) {
-  return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
-}
-
-// One element of the row joins the running state (reference raised first if needed).
-__device__ __forceinline__ void lse_push(Lse& st, float z) {
-  lse_raise(st, z * kLog2e);
-  lse_add(st, z);
-}
 
 template <int DT>
 __device__ __forceinline__ void lse_push_vec(Lse& st, const uint4& q) {
@@ -132,32 +94,6 @@ k_rowstats(RowMap map, int S, Workspace ws) {
     for (int w = 1; w < kWaves; ++w) t = lse_merge(t, sh[w]);
     ws.part1[(size_t)rho * kMaxSplit + s] = make_float4(t.m, t.s, t.u, 0.f);   // folded by the next kernel
   }
-}
-
-// Fold of the S slice results of one row by one wavefront (all lanes return the same): common
-// reference, plain sums, then the row's log2-sum-exp and entropy in double precision.
-__device__ __forceinline__ RowResult fold_row(const Workspace& ws, int rho, int S) {
-  const int lane = threadIdx.x & 63;
-  Lse t = lse_empty();
-  if (lane < S) {
-    const float4 p = ws.part1[(size_t)rho * kMaxSplit + lane];
-    t = Lse{p.x, p.y, p.z};
-  }
-  const float M = wave_max_f(t.m), d = t.m - M, f = ex2(d);
-  const float sw = wave_sum_f(t.s * f), uw = wave_sum_f((t.u + d * t.s) * f);
-  const bool ok = (sw > 0.f) && (sw < INFINITY) && (fabsf(uw) < INFINITY) && (M > kNegHuge) && (M < INFINITY);
-  RowResult res;
-  if (ok) {
-    const double l2s = log2_acc(sw);
-    res.lse2 = (double)M + l2s;
-    res.H = (float)(kLn2 * (l2s - (double)uw / (double)sw));
-    res.bad = 0;
-  } else {
-    res.lse2 = NAN;
-    res.H = NAN;
-    res.bad = 1;
-  }
-  return res;
 }
 
 // Draft-entropy epilogue (stop rule of Algorithm 1's drafting loop): one wavefront per row.

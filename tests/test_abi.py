@@ -25,7 +25,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_symbols()
-    assert {"adasd_draft_entropy", "adasd_verify", "adasd_update_thresholds", "adasd_workspace_bytes",
+    assert {"adasd_draft_entropy", "adasd_draft_step", "adasd_verify", "adasd_update_thresholds", "adasd_workspace_bytes",
             "adasd_workspace_init", "adasd_state_init", "adasd_strerror", "adasd_version"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n

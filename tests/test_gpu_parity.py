@@ -485,6 +485,97 @@ def test_draft_entropy_rule(am, wl, oracle):
     assert stop3.cpu().numpy()[ok].sum() == 0
 
 
+# ------------------------------------------------------------------------------- drafting step with the token draw
+def _draft_step_case(am, oracle, z, **kw):
+    B, V = z.shape
+    ws = am.Workspace(B, 1, V, z.dtype)
+    dev = {k: (None if v is None else torch.as_tensor(v).cuda()) for k, v in kw.items()
+           if k in ("T_G", "active", "seq_id", "rounds")}
+    if dev.get("seq_id") is not None:
+        dev["seq_id"] = torch.tensor(np.asarray(kw["seq_id"], np.uint32).view(np.int32)).cuda()
+    if dev.get("rounds") is not None:
+        dev["rounds"] = torch.tensor(np.asarray(kw["rounds"], np.uint32).view(np.int32)).cuda()
+    scal = {k: kw[k] for k in ("step", "k_max", "seed", "round0") if k in kw}
+    H, stop, tok, st = am.draft_step(z.cuda(), ws, **dev, **scal)
+    He, stope = am.draft_entropy(z.cuda(), ws, T_G=dev.get("T_G"), active=dev.get("active"),
+                                 step=scal.get("step", 0), k_max=scal.get("k_max", 1 << 30))
+    torch.cuda.synchronize()
+    # entropy and stop flag are those of the entropy-only call, bit for bit
+    assert torch.equal(H.view(torch.int32), He.view(torch.int32)) and torch.equal(stop, stope)
+    ref_tok, gap = oracle.draft_sample(z, active=kw.get("active"), step=scal.get("step", 0),
+                                       seed=scal.get("seed", 0), seq_id=kw.get("seq_id"),
+                                       rounds=kw.get("rounds"), round0=scal.get("round0", 0))
+    return H.cpu().numpy(), stop.cpu().numpy(), tok.cpu().numpy(), st.cpu().numpy(), ref_tok, gap
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("V", [8, 100, 1001, 4096, 20011, 128256])
+def test_draft_step_draws_the_oracles_tokens(am, wl, oracle, dtype, V):
+    g = torch.Generator().manual_seed(V + 1)
+    B = 19
+    z = (torch.randn(B, V, generator=g) * torch.linspace(0.5, 5, B).reshape(B, 1)).to(dtype)
+    z[3, : V // 2] = float("-inf")                       # masked tokens are never drawn
+    active = np.ones(B, np.uint8); active[4] = 0
+    seq = np.arange(B, dtype=np.uint32) * 7919 + 4000000000 % 977
+    rounds = np.arange(B, dtype=np.uint32) % 3
+    tg = (torch.rand(B, generator=g) * 10).numpy().astype(np.float32)
+    H, stop, tok, st, ref_tok, gap = _draft_step_case(am, oracle, z, T_G=tg, active=active, seq_id=seq,
+                                                      rounds=rounds, step=5, k_max=20, seed=0xABCDEF0123)
+    assert np.array_equal(tok, ref_tok), (tok, ref_tok, gap)
+    assert tok[4] == -1 and H[4] == 0 and stop[4] == 0
+    assert tok[3] >= V // 2
+    assert (st & ~16 == 0).all()
+    Href, sref = oracle.draft_entropy(z, T_G=tg, active=active, step=5, k_max=20)
+    assert G.close(H, Href).all()
+
+
+def test_draft_step_unaligned_rows_and_broken_rows(am, wl, oracle):
+    g = torch.Generator().manual_seed(3)
+    B, V = 6, 4099                                       # odd row length: most rows are not 16-byte aligned
+    z = (torch.randn(B, V, generator=g) * 2).to(torch.bfloat16)
+    z[1, 7] = float("nan")
+    z[2] = float("-inf")
+    z[3, 9] = float("inf")
+    z[4] = float("-inf"); z[4, 4000] = 1.0               # one-hot
+    H, stop, tok, st, ref_tok, gap = _draft_step_case(am, oracle, z, step=0, k_max=4, seed=9)
+    assert np.array_equal(tok, ref_tok)
+    assert list(tok[1:5]) == [-1, -1, -1, 4000]
+    assert all(st[b] & am.binding.ST_NONFINITE for b in (1, 2, 3)) and st[0] & ~16 == 0
+    assert all(stop[b] == 1 for b in (1, 2, 3)) and H[4] == 0.0
+
+
+@pytest.mark.parametrize("dtype,V", [(torch.bfloat16, 128256), (torch.float32, 4104), (torch.bfloat16, 4107)],
+                         ids=["bf16-headline", "f32-small", "bf16-unaligned"])
+def test_draft_step_near_ties_are_settled_in_float64(am, wl, oracle, dtype, V):
+    g = torch.Generator().manual_seed(V + 5)
+    z = (torch.randn(1, V, generator=g) * 2.5).to(dtype)
+    n = 200000 if V < 10000 else 6000
+    ref_tok, gap = oracle.draft_sample(z, step=2, seed=77, round0=3, shared_row=n)
+    close_call = np.flatnonzero(gap < (1e-4 if V < 10000 else 1e-3))[:24]
+    assert len(close_call) >= 2, "no near tie among the draws: widen the search"
+    B = len(close_call)
+    rows = z.repeat(B, 1).contiguous()
+    H, stop, tok, st, ref_b, gap_b = _draft_step_case(am, oracle, rows, seq_id=close_call.astype(np.uint32),
+                                                      step=2, seed=77, round0=3)
+    assert np.array_equal(ref_b, ref_tok[close_call])
+    assert np.array_equal(tok, ref_b), (tok, ref_b, gap_b)
+    print(f"[draft near ties] V={V}: {B} draws, {(st & 16 != 0).sum()} settled in float64, gaps {np.sort(gap_b)[:4]}", flush=True)
+    assert V > 10000 or (st & 16 != 0).sum() >= 1        # the closest draws of the short search at the large V may still be decidable in float
+
+
+def test_draft_step_argument_errors(am):
+    ws = am.Workspace(2, 1, 64, torch.float32)
+    z = torch.zeros(2, 64, device="cuda")
+    with pytest.raises(am.AdasdError) as e:
+        am.draft_step(z, ws, step=70000)
+    assert e.value.code == -1
+    small = am.Workspace(1, 1, 64, torch.float32)
+    with pytest.raises(am.AdasdError) as e:
+        am.draft_step(torch.zeros(4, 64, device="cuda"), small)
+    assert e.value.code == -4
+    am.draft_step(torch.zeros(0, 64, device="cuda"), ws)          # B = 0 is a no-op
+
+
 # ------------------------------------------------------------------------------- update + closed loop
 @pytest.mark.parametrize("B,K,cap", [(9, 6, 12), (7, 64, 100)])   # 64: the largest window, every lane a position
 def test_update_matches_oracle_and_state_round_trip(am, wl, oracle, B, K, cap):
