@@ -57,6 +57,7 @@ constexpr size_t kRegionBytes[] = {
     (size_t)kMaxSplit * sizeof(float2),                   // part2
     sizeof(SamplePlan),                                   // plan
     (size_t)kMaxSampleSplit * sizeof(Top2),               // part3
+    sizeof(PosRecord),                                    // pos_rec
 };
 constexpr size_t per_position_bytes() {
   size_t t = 0;
@@ -66,11 +67,11 @@ constexpr size_t per_position_bytes() {
 }  // namespace
 
 size_t workspace_bytes_for(size_t positions) {
-  return kHeaderBytes + (positions + 1) * per_position_bytes() + 8 * 256;
+  return kHeaderBytes + (positions + 1) * per_position_bytes() + 9 * 256;
 }
 
 size_t workspace_layout(size_t ws_bytes, Workspace* ws, void* base) {
-  const size_t slack = kHeaderBytes + 8 * 256;
+  const size_t slack = kHeaderBytes + 9 * 256;
   if (ws_bytes <= slack) return 0;
   const size_t cap = (ws_bytes - slack) / per_position_bytes();
   if (ws && cap > 0) {
@@ -93,6 +94,7 @@ size_t workspace_layout(size_t ws_bytes, Workspace* ws, void* base) {
     ws->part2 = reinterpret_cast<float2*>(take(cap * kRegionBytes[5]));
     ws->plan = reinterpret_cast<SamplePlan*>(take(cap * kRegionBytes[6]));
     ws->part3 = reinterpret_cast<Top2*>(take(cap * kRegionBytes[7]));
+    ws->pos_rec = reinterpret_cast<PosRecord*>(take(cap * kRegionBytes[8]));
     ws->bytes = off;
   }
   return cap;

@@ -16,6 +16,25 @@ __global__ void __launch_bounds__(kBlock) k_decide(DecideArgs a, UpdateArgs upd,
   if (upd.B > 0 && threadIdx.x < 64) update_sequence(upd, blockIdx.x, threadIdx.x, sh.first_reject, sh.k_b);
 }
 
+// Long histories: one workgroup per candidate position, grid (k_max, sequences).
+template <int DT, bool INLOOP>
+__global__ void __launch_bounds__(kBlock) k_decide_wide(DecideArgs a, UpdateArgs upd, Workspace ws) {
+  warm_kernargs<sizeof(DecideArgs) + sizeof(UpdateArgs) + sizeof(Workspace)>();
+  __shared__ DecideShared sh;
+  __shared__ WideShared wsh;
+  // The launch is sized for long lists (the host only knows their capacity); a sequence whose lists are
+  // still short is cheaper in the one-workgroup form, so its first workgroup takes that and the others leave.
+  const int b = blockIdx.y;
+  const int n_long = min(max(max(a.nA[b], a.nR[b]), 0), a.cap);
+  if (n_long < kWideMin) {
+    if (blockIdx.x != 0) return;
+    decide_sequence<DT, INLOOP>(a, ws, b, sh);
+    if (upd.B > 0 && threadIdx.x < 64) update_sequence(upd, b, threadIdx.x, sh.first_reject, sh.k_b);
+    return;
+  }
+  decide_position_wide<DT, INLOOP>(a, upd, ws, ws.pos_rec, b, blockIdx.x, sh, wsh);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Update step: one wavefront per sequence, one lane per candidate position (k_max <= 64).  Every lane
 // reads its position's distance at once; accepted positions that pass the open-interval filter are
@@ -50,7 +69,19 @@ __global__ void __launch_bounds__(256) k_zero(uint32_t* p, size_t n) {
 
 hipError_t launch_decide(const DecideArgs& a, const UpdateArgs& upd, const Workspace& ws, hipStream_t st) {
   if (a.map.B <= 0) return hipSuccess;
-  const dim3 grid(a.map.B), block(kBlock);
+  const dim3 block(kBlock);
+  if (a.cap >= kWideCap && a.map.K > 0 && !a.relaxed_off && a.LA && a.LR && a.nA && a.nR) {
+    const dim3 grid(a.map.K, a.map.B);
+    if (a.dt == ADASD_BF16) {
+      if (a.list_update) launch_kernel(k_decide_wide<ADASD_BF16, true>, grid, block, st, a, upd, ws);
+      else launch_kernel(k_decide_wide<ADASD_BF16, false>, grid, block, st, a, upd, ws);
+    } else {
+      if (a.list_update) launch_kernel(k_decide_wide<ADASD_F32, true>, grid, block, st, a, upd, ws);
+      else launch_kernel(k_decide_wide<ADASD_F32, false>, grid, block, st, a, upd, ws);
+    }
+    return hipGetLastError();
+  }
+  const dim3 grid(a.map.B);
   if (a.dt == ADASD_BF16) {
     if (a.list_update) launch_kernel(k_decide<ADASD_BF16, true>, grid, block, st, a, upd, ws);
     else launch_kernel(k_decide<ADASD_BF16, false>, grid, block, st, a, upd, ws);

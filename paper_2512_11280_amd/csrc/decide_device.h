@@ -98,6 +98,56 @@ struct DecideShared {
   uint32_t status;
 };
 
+// Everything a candidate position needs from memory, and its two uniforms.
+struct PosLoad {
+  int x;
+  bool x_ok;
+  float zp, zq, p0, p1;
+  RowResult rp, rq;
+  double log_u1, u2;
+};
+
+template <int DT>
+__device__ __forceinline__ PosLoad load_position(const DecideArgs& a, const Workspace& ws, int b, int i, uint32_t rnd,
+                                                 uint32_t seq) {
+  const int l32 = threadIdx.x & 31, K = a.map.K;
+  PosLoad L;
+  const size_t o = (size_t)b * K + i;
+  L.x = a.draft_tokens[o];
+  L.x_ok = L.x >= 0 && L.x < a.map.V;
+  const char* prow = a.map.base[0] +
+      ((int64_t)b * a.map.seq_stride[0] + (int64_t)i * a.map.pos_stride[0]) * Elem<DT>::bytes;
+  const char* qrow = a.map.base[1] +
+      ((int64_t)b * a.map.seq_stride[1] + (int64_t)i * a.map.pos_stride[1]) * Elem<DT>::bytes;
+  L.zp = load_elem<DT>(prow, L.x_ok ? L.x : 0);
+  L.zq = load_elem<DT>(qrow, L.x_ok ? L.x : 0);
+  L.rp = ws.rows[2 * o];
+  L.rq = ws.rows[2 * o + 1];
+  L.p0 = L.p1 = 0.f;
+  if (a.jsd_split > 0) {
+    const float* part = reinterpret_cast<const float*>(ws.part2 + o * kMaxSplit);
+    L.p0 = l32 < a.jsd_split ? part[2 * l32] : 0.f;
+    L.p1 = l32 + 32 < a.jsd_split ? part[2 * (l32 + 32)] : 0.f;
+  }
+  const U4 r = philox4x32_10(0u, (uint32_t)i, rnd, seq, a.seed_lo, a.seed_hi);
+  // u1 = (w + 0.5) / 2^24 rounded to float: 3e-8 relative, i.e. 3e-8 absolute on its logarithm
+  L.log_u1 = kLn2 * log2_acc((float)(((double)(r.w[0] >> 8) + 0.5) * (1.0 / 16777216.0)));
+  L.u2 = ((double)(r.w[1] >> 8) + 0.5) * (1.0 / 16777216.0);
+  return L;
+}
+
+// Two-kernel path: the JS kernel left one partial sum per slice.  Half a wavefront adds them up in a
+// fixed tree, corrects the common scale to first order (the weights were formed with the float
+// roundings cp, cq of the normalisers, i.e. they are p(1+c), q(1+c') with c = ln2 (lse2_p - cp)) and
+// takes the root.
+__device__ __forceinline__ float fold_distance(const PosLoad& L) {
+  const double A = half_sum_d((double)L.p0 + (double)L.p1);
+  const double c0 = kLn2 * (L.rp.lse2 - (double)(float)L.rp.lse2), c1 = kLn2 * (L.rq.lse2 - (double)(float)L.rq.lse2);
+  double D = 0.5 * A * (1.0 - 0.5 * (c0 + c1));   // bits
+  D = fmin(fmax(D, 0.0), 1.0);
+  return (L.rp.bad || L.rq.bad) ? NAN : (float)sqrt(D);
+}
+
 // The decisions of one sequence by one workgroup of 256 threads.  INLOOP: the accepted list grows
 // inside the verification loop (Algorithm 1): position i sees the list of the state followed by the
 // distances of positions 0..i-1 of this round that pass the open-interval filter, up to the capacity.
@@ -119,54 +169,11 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
   const uint32_t seq = a.seq_id ? a.seq_id[b] : (uint32_t)b;
   const uint32_t rnd = a.round ? a.round[b] : a.round0;
 
-  // Everything a candidate position needs from memory, and its two uniforms.  The first position of
-  // each group is requested before the list moments are formed, so the two chains of dependent
-  // loads (token -> its logits, list lengths -> samples) run side by side.
-  struct PosLoad {
-    int x;
-    bool x_ok;
-    float zp, zq, p0, p1;
-    RowResult rp, rq;
-    double log_u1, u2;
-  };
-  auto load_pos = [&](int i) {
-    PosLoad L;
-    const size_t o = (size_t)b * K + i;
-    L.x = a.draft_tokens[o];
-    L.x_ok = L.x >= 0 && L.x < a.map.V;
-    const char* prow = a.map.base[0] +
-        ((int64_t)b * a.map.seq_stride[0] + (int64_t)i * a.map.pos_stride[0]) * Elem<DT>::bytes;
-    const char* qrow = a.map.base[1] +
-        ((int64_t)b * a.map.seq_stride[1] + (int64_t)i * a.map.pos_stride[1]) * Elem<DT>::bytes;
-    L.zp = load_elem<DT>(prow, L.x_ok ? L.x : 0);
-    L.zq = load_elem<DT>(qrow, L.x_ok ? L.x : 0);
-    L.rp = ws.rows[2 * o];
-    L.rq = ws.rows[2 * o + 1];
-    L.p0 = L.p1 = 0.f;
-    if (a.jsd_split > 0) {
-      const float* part = reinterpret_cast<const float*>(ws.part2 + o * kMaxSplit);
-      L.p0 = l32 < a.jsd_split ? part[2 * l32] : 0.f;
-      L.p1 = l32 + 32 < a.jsd_split ? part[2 * (l32 + 32)] : 0.f;
-    }
-    const U4 r = philox4x32_10(0u, (uint32_t)i, rnd, seq, a.seed_lo, a.seed_hi);
-    // u1 = (w + 0.5) / 2^24 rounded to float: 3e-8 relative, i.e. 3e-8 absolute on its logarithm
-    L.log_u1 = kLn2 * log2_acc((float)(((double)(r.w[0] >> 8) + 0.5) * (1.0 / 16777216.0)));
-    L.u2 = ((double)(r.w[1] >> 8) + 0.5) * (1.0 / 16777216.0);
-    return L;
-  };
+  // The first position of each group is requested before the list moments are formed, so the two
+  // chains of dependent loads (token -> its logits, list lengths -> samples) run side by side.
+  auto load_pos = [&](int i) { return load_position<DT>(a, ws, b, i, rnd, seq); };
   PosLoad first;
   if (grp < kb) first = load_pos(grp);
-
-  // Two-kernel path: the JS kernel left one partial sum per slice.  The group adds them up in a fixed
-  // tree, corrects the common scale to first order (the weights were formed with the float roundings
-  // cp, cq of the normalisers, i.e. they are p(1+c), q(1+c') with c = ln2 (lse2_p - cp)) and takes the root.
-  auto fold_distance = [&](const PosLoad& L) {
-    const double A = half_sum_d((double)L.p0 + (double)L.p1);
-    const double c0 = kLn2 * (L.rp.lse2 - (double)(float)L.rp.lse2), c1 = kLn2 * (L.rq.lse2 - (double)(float)L.rq.lse2);
-    double D = 0.5 * A * (1.0 - 0.5 * (c0 + c1));   // bits
-    D = fmin(fmax(D, 0.0), 1.0);
-    return (L.rp.bad || L.rq.bad) ? NAN : (float)sqrt(D);
-  };
 
   // ---- Bayesian test set-up: both lists need enough samples and spread (else P(A|d) = 0).
   // One pass over both lists (moments about the first element), one workgroup reduction.
@@ -375,12 +382,11 @@ namespace adasd {
 // by one wavefront, one lane per candidate position (k_max <= 64).  Every lane reads its position's
 // distance at once; accepted positions that pass the open-interval filter are appended in position
 // order (rank = number of passing positions before it, from a ballot).
-__device__ inline void update_sequence(const UpdateArgs& a, int b, int lane, int r, int kb) {
+// d: the lane's distance (lanes <= r, below kb), H: the draft entropy of the rejected position (lane r).
+__device__ inline void update_sequence_core(const UpdateArgs& a, int b, int lane, int r, int kb, float d, float H) {
   const int nA = a.nA[b], nR = a.nR[b];
   const float lo = a.d_eps, hi = 1.0f - a.d_eps;
-  float d = 0.f, H = 0.f;
-  if (lane <= r && lane < kb) d = a.d_js[(size_t)b * a.K + lane];
-  if (lane == r && r < kb) H = a.H_q[(size_t)b * a.K + r];
+  if (!(lane <= r && lane < kb)) d = 0.f;
   const bool pass = d > lo && d < hi;                       // NaN fails both comparisons
   uint32_t st = 0;
   // accepted positions 0 .. r-1
@@ -409,6 +415,292 @@ __device__ inline void update_sequence(const UpdateArgs& a, int b, int lane, int
   const int cnt = a.ent_cnt[b];
   a.T_G[b] = cnt > 0 ? (float)(a.ent_sum[b] / (double)cnt) : 0.f;
   if (a.status && st) a.status[b] |= st;
+}
+
+__device__ inline void update_sequence(const UpdateArgs& a, int b, int lane, int r, int kb) {
+  float d = 0.f, H = 0.f;
+  if (lane <= r && lane < kb) d = a.d_js[(size_t)b * a.K + lane];
+  if (lane == r && r < kb) H = a.H_q[(size_t)b * a.K + r];
+  update_sequence_core(a, b, lane, r, kb, d, H);
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Long histories.  The cost of the Bayesian test grows with the lists (Section 4.4 flags it): with
+// thousands of samples per list one workgroup per sequence and half a wavefront per position is far
+// too little.  Here one workgroup of 256 threads takes ONE position: every thread walks a stride of
+// both lists once (running maximum and rescaled sum, so no separate pass for the maximum), the
+// workgroups of a sequence leave one record per position, and the one that arrives last takes the
+// sequence's decisions (first rejection, sampling plan, status, update step).
+// ---------------------------------------------------------------------------------------------
+struct WideShared {
+  double m[kWaves], s[kWaves];
+  int last;
+  int n_pass;           // in-loop appends: earlier positions of this round that pass the filter
+};
+
+// ln [ p(d | list) P(list) ] by the whole workgroup; the list continues in X (nx samples).
+__device__ inline double block_log_joint(double d, const float* L, int n, const float* X, int nx, const Kde& k,
+                                         WideShared& w) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nt = n + nx;
+  double m = -INFINITY, s = 0.0;
+  constexpr int U = 16;                    // samples per thread in flight: one workgroup walks the list alone, so the
+                                           // latency of a load is only hidden by the thread's own other loads
+  for (int base = 0; base < nt; base += U * kBlock) {
+    float x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = min(base + tid + u * kBlock, nt - 1);
+      x[u] = j < n ? L[j] : X[j - n];
+    }
+    // exponents of the batch, its maximum joins the running one, then ONE rescale of the old sum
+    double t[U];
+    double hi = m;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const double e = d - (double)x[u];
+      t[u] = base + tid + u * kBlock < nt ? -(e * e) * k.inv2h2 : -INFINITY;
+      hi = fmax(hi, t[u]);
+    }
+    if (hi > -INFINITY) {                  // (a thread past the end of the list has nothing to add)
+      // all exponents are <= 0; with m = -inf the old sum is 0 and its factor 2^-inf = 0
+      float add = 0.f;
+#pragma unroll
+      for (int u = 0; u < U; ++u) add += ex2((float)((t[u] - hi) * 1.44269504088896340736));
+      s = s * (double)ex2((float)((m - hi) * 1.44269504088896340736)) + (double)add;
+      m = hi;
+    }
+  }
+  // wavefront, then workgroup: common maximum, rescaled sums (a thread without samples has s = 0)
+  double M = half_max_d(m);
+  M = fmax(M, __shfl_xor(M, 32));
+  double sc = m > -INFINITY ? s * (double)ex2((float)((m - M) * 1.44269504088896340736)) : 0.0;
+  sc = half_sum_d(sc);
+  sc += __shfl_xor(sc, 32);
+  __syncthreads();
+  if (lane == 0) {
+    w.m[wave] = M;
+    w.s[wave] = sc;
+  }
+  __syncthreads();
+  double Mb = w.m[0];
+#pragma unroll
+  for (int q = 1; q < kWaves; ++q) Mb = fmax(Mb, w.m[q]);
+  double total = 0.0;
+#pragma unroll
+  for (int q = 0; q < kWaves; ++q)
+    total += w.m[q] > -INFINITY ? w.s[q] * (double)ex2((float)((w.m[q] - Mb) * 1.44269504088896340736)) : 0.0;
+  return Mb + kLn2 * log2_acc((float)total) - k.log_norm;
+}
+
+template <int DT, bool INLOOP>
+__device__ void decide_position_wide(const DecideArgs& a, const UpdateArgs& upd, const Workspace& ws,
+                                     PosRecord* records, int b, int i, DecideShared& sh, WideShared& wsh) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = tid & 31, grp = tid >> 5;
+  constexpr int kGroups = kBlock / 32;
+  const int K = a.map.K;
+  int kb = K;
+  uint32_t st_seq = 0;
+  if (a.map.draft_len) {
+    const int raw = a.map.draft_len[b];
+    kb = min(max(raw, 0), K);
+    if (raw != kb) st_seq |= ADASD_ST_BAD_LENGTH;
+  }
+  const uint32_t seq = a.seq_id ? a.seq_id[b] : (uint32_t)b;
+  const uint32_t rnd = a.round ? a.round[b] : a.round0;
+  const size_t o = (size_t)b * K + i;
+
+  PosRecord rec{0, 0u, 0.f, 0.f};
+  if (i >= kb) {
+    if (tid == 0) {
+      if (a.H_p) a.H_p[o] = 0.f;
+      a.H_q[o] = 0.f;
+      a.d_js[o] = 0.f;
+      if (a.p_accept) a.p_accept[o] = 0.f;
+      if (a.accept_mask) a.accept_mask[o] = 0;
+    }
+  } else {
+    const PosLoad L = load_position<DT>(a, ws, b, i, rnd, seq);
+    const bool bad = L.rp.bad || L.rq.bad;
+    const int min_n = a.kde_min_n < 2 ? 2 : a.kde_min_n;
+    int nA = 0, nR = 0;
+    const float* LA = nullptr;
+    const float* LR = nullptr;
+    if (a.LA && a.LR && a.nA && a.nR) {
+      nA = min(max(a.nA[b], 0), a.cap);
+      nR = min(max(a.nR[b], 0), a.cap);
+      LA = a.LA + (size_t)b * a.cap;
+      LR = a.LR + (size_t)b * a.cap;
+    }
+    int ne = 0;                            // in-loop appends this position sees
+    if (INLOOP) {
+      // distances of the earlier positions (each workgroup of the sequence forms them for itself)
+      for (int j = grp; j < i; j += kGroups) {
+        const PosLoad Lj = load_position<DT>(a, ws, b, j, rnd, seq);
+        float dv;
+        if (a.jsd_split > 0) dv = fold_distance(Lj);
+        else dv = (Lj.rp.bad || Lj.rq.bad) ? NAN : a.d_js[(size_t)b * K + j];
+        if (l32 == 0) sh.dist[j] = dv;
+      }
+      __syncthreads();
+      if (wave == 0) {
+        const float dv = lane < i ? sh.dist[lane] : NAN;
+        const bool pass = dv > a.d_eps && dv < 1.0f - a.d_eps;
+        const unsigned long long mask = __ballot(pass);
+        if (pass) sh.extra[__popcll(mask & ((1ull << lane) - 1ull))] = dv;
+        if (lane == 0) wsh.n_pass = __popcll(mask);
+      }
+      __syncthreads();
+      ne = LA ? min(wsh.n_pass, max(a.cap - nA, 0)) : 0;
+    }
+    float d_out;
+    if (a.jsd_split > 0) {
+      d_out = fold_distance(L);
+      if (tid == 0) a.d_js[o] = d_out;
+    } else {
+      d_out = bad ? NAN : a.d_js[o];
+    }
+    const double d = (double)d_out;
+    const int n_i = nA + ne;
+    double PA = 0.0;
+    if (!a.relaxed_off && !bad && LA && n_i >= min_n && nR >= min_n) {      // uniform over the workgroup
+      const double cA = nA > 0 ? (double)LA[0] : (double)sh.extra[0], cR = (double)LR[0];
+      double m[4] = {0.0, 0.0, 0.0, 0.0};
+      constexpr int U = 16;                // loads in flight per thread, as in block_log_joint
+      for (int base = 0; base < n_i; base += U * kBlock) {
+        float x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int j = min(base + tid + u * kBlock, n_i - 1);
+          x[u] = j < nA ? LA[j] : sh.extra[j - nA];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const double e = base + tid + u * kBlock < n_i ? (double)x[u] - cA : 0.0;
+          m[0] += e;
+          m[1] += e * e;
+        }
+      }
+      for (int base = 0; base < nR; base += U * kBlock) {
+        float x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = LR[min(base + tid + u * kBlock, nR - 1)];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const double e = base + tid + u * kBlock < nR ? (double)x[u] - cR : 0.0;
+          m[2] += e;
+          m[3] += e * e;
+        }
+      }
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        m[x] = half_sum_d(m[x]);
+        m[x] += __shfl_xor(m[x], 32);
+      }
+      if (lane == 0) {
+#pragma unroll
+        for (int x = 0; x < 4; ++x) sh.mom[wave][x] = m[x];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int x = 0; x < 4; ++x) m[x] = (sh.mom[0][x] + sh.mom[1][x]) + (sh.mom[2][x] + sh.mom[3][x]);
+      Kde kA, kR;
+      if (kde_constants(m[0], m[1], n_i, nR, a.bw_rule, &kA) && kde_constants(m[2], m[3], nR, n_i, a.bw_rule, &kR)) {
+        const double ja = block_log_joint(d, LA, nA, sh.extra, ne, kA, wsh);
+        const double jr = block_log_joint(d, LR, nR, nullptr, 0, kR, wsh);
+        PA = 1.0 / (1.0 + (double)ex2((float)((jr - ja) * 1.44269504088896340736)));
+      }
+    }
+    if (tid == 0) {
+      rec.d = d_out;
+      if (bad) {
+        if (a.H_p) a.H_p[o] = NAN;
+        a.H_q[o] = NAN;
+        a.d_js[o] = NAN;
+        if (a.p_accept) a.p_accept[o] = NAN;
+        if (a.accept_mask) a.accept_mask[o] = 0;
+        rec.bits = 2;
+        rec.status = ADASD_ST_NONFINITE;
+        rec.d = NAN;
+      } else {
+        int base = 0;
+        if (!L.x_ok) {
+          rec.status |= ADASD_ST_BAD_TOKEN;
+        } else if (a.base_test == 1) {
+          base = L.log_u1 < (double)L.zp - L.rp.lse2 * kLn2;
+        } else {
+          double log_ratio = ((double)L.zp - L.rp.lse2 * kLn2) - ((double)L.zq - L.rq.lse2 * kLn2);
+          if (log_ratio > 0.0) log_ratio = 0.0;
+          base = L.log_u1 < log_ratio;
+        }
+        const int relaxed = a.reject_rule == 1 ? (PA >= 0.5) : (L.u2 < PA);
+        if (a.p_accept) a.p_accept[o] = (float)PA;
+        if (a.accept_mask) a.accept_mask[o] = (uint8_t)(base | (relaxed << 1));
+        rec.bits = (base || relaxed) ? 1 : 0;
+      }
+    }
+  }
+  // ---- the position's record, then the arrival counter of the sequence
+  if (tid == 0) {
+    PosRecord* dst = records + o;
+    st_agent(&dst->bits, rec.bits);
+    st_agent(reinterpret_cast<int*>(&dst->status), (int)rec.status);
+    st_agent(&dst->d, rec.d);
+    publish_barrier();
+    const int ticket = atomicAdd(&ws.ticket2[b], 1);
+    wsh.last = ticket == K - 1;
+  }
+  __syncthreads();
+  if (!wsh.last || wave != 0) return;
+
+  // ---- last workgroup of the sequence, one wavefront, one lane per position
+  int bits = 0;
+  uint32_t pst = 0;
+  float dl = 0.f;
+  if (lane < K) {
+    const PosRecord* src = records + (size_t)b * K + lane;
+    bits = ld_agent(&src->bits);
+    pst = (uint32_t)ld_agent(reinterpret_cast<const int*>(&src->status));
+    dl = ld_agent(&src->d);
+  }
+  const unsigned long long rejected = __ballot(lane < kb && !(bits & 1));
+  const int r = rejected ? __ffsll((long long)rejected) - 1 : kb;
+  uint32_t st_all = pst;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) st_all |= __shfl_xor(st_all, off);
+  const int bad_r = __shfl(bits, r < 64 ? r : 63) & 2;
+  if (lane == 0) {
+    a.n_accept[b] = r;
+    SamplePlan plan;
+    plan.row = r;
+    plan.excluded = -1;
+    if (r < kb) {
+      plan.residual = 1;
+      if (a.base_test == 1) {
+        const int x = a.draft_tokens[(size_t)b * K + r];
+        const bool x_ok = x >= 0 && x < a.map.V;
+        plan.residual = x_ok ? 2 : 0;
+        plan.excluded = x_ok ? x : -1;
+      }
+      plan.valid = !bad_r;
+      plan.lse2_p = ws.rows[2 * ((size_t)b * K + r)].lse2;
+      plan.lse2_q = ws.rows[2 * ((size_t)b * K + r) + 1].lse2;
+    } else {
+      plan.residual = 0;
+      plan.valid = 1;
+      plan.lse2_p = 0.0;
+      plan.lse2_q = 0.0;
+    }
+    ws.plan[b] = plan;
+    a.status[b] = st_seq | st_all;
+    __hip_atomic_store(&ws.ticket2[b], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  if (upd.B > 0) {
+    publish_barrier();           // the status word above is read and OR-ed by another lane below
+    float H = 0.f;
+    if (lane == r && r < kb) H = upd.H_q[(size_t)b * K + r];   // written by the statistics stage (an earlier kernel)
+    update_sequence_core(upd, b, lane, r, kb, dl, H);
+  }
 }
 
 }  // namespace adasd

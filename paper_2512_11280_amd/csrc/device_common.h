@@ -288,6 +288,13 @@ struct SamplePlan {  // one per sequence, written by the decision kernel
   double lse2_p, lse2_q;
 };
 
+struct PosRecord {   // outcome of one position, left by the long-history decision kernel for the sequence's last workgroup
+  int32_t bits;      // 1: position accepted, 2: row pair broken
+  uint32_t status;
+  float d;           // the distance as written to d_js
+  float pad;
+};
+
 struct Top2 {        // running best / runner-up of the Gumbel keys (log2 domain)
   float k1; int32_t i1;
   float k2; int32_t i2;

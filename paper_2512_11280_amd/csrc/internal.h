@@ -11,6 +11,8 @@
 
 namespace adasd {
 
+constexpr int kWideCap = 512;       // list capacity from which the decision stage is launched with a workgroup per position
+constexpr int kWideMin = 384;       // list length from which a sequence actually uses them
 constexpr int kMaxSplit = 64;        // vocabulary slices per row (statistics kernels)
 constexpr int kMaxSampleSplit = 128; // vocabulary slices per sequence (sampling kernel)
 constexpr int kMaxFusedSplit = 128;  // wavefront slices per row pair in the fused statistics kernel
@@ -39,6 +41,7 @@ struct Workspace {
   int32_t* fused_cnt; // [positions][kCntStride] arrival counters of the fused kernel, one per 128-byte line
   uint64_t* fused_slots; // [positions][kMaxFusedSplit][kSlotWords] self-validating hand-off words, zero between calls
   uint64_t* fused_norm;  // [positions][kSlotWords] folded triples of both rows, published by the position's leader
+  PosRecord* pos_rec; // [positions] outcomes of the positions (long-history decision kernel)
   size_t bytes;
 };
 

@@ -324,6 +324,72 @@ def test_literal_variant_status_and_float64_path(am, wl, oracle):
     assert (out.next_token.cpu().numpy()[:-1] != 3).all()
 
 
+# ------------------------------------------------------------------------------- long histories
+@pytest.mark.parametrize("n_hist,cap", [(64, 512), (700, 1024), (5000, 5003), (40000, 40100)])
+@pytest.mark.parametrize("opt", [dict(), dict(list_update=1, base_test=1), dict(bw_rule=1, reject_rule=1)],
+                         ids=["default", "literal", "scott-map"])
+def test_long_history_lists_take_the_workgroup_per_position_path(am, wl, oracle, n_hist, cap, opt, path):
+    """From a list capacity of 512 on, the decision stage gives every position a workgroup of its own."""
+    if path == 2 and n_hist != 700:
+        pytest.skip("the statistics path does not matter here; one size covers it")
+    batch = wl.config_batched(B=5, k=6, V=8192, seed=300 + n_hist, cap=cap)
+    g = torch.Generator().manual_seed(n_hist)
+    batch.state = wl.threshold_state(batch.B, cap, g, n_hist=n_hist)
+    batch.state["nA"][1] = max(n_hist - 37, 0)                 # lists of different lengths
+    batch.state["nR"][2] = max(n_hist // 2, 2)
+    batch.state["nA"][3] = cap - 2                             # nearly full: in-loop appends hit the capacity
+    batch.state["LA"][3, n_hist:cap - 2] = batch.state["LA"][3, :cap - 2 - n_hist] if cap - 2 - n_hist <= n_hist else 0.3
+    batch.draft_len = torch.tensor([6, 6, 4, 6, 0], dtype=torch.int32)
+    options = am.Options(**opt)
+    out, _, _ = G.run_gpu(am, batch, options=options, stats_path=path)
+    ref = G.run_oracle(oracle, batch, options=options)
+    rep = G.compare_verify(out, ref)
+    _report(f"long history n={n_hist} {opt}", rep)
+    assert (ref["p_accept"] > 0).any()
+
+
+def test_long_history_with_the_update_in_the_same_call_and_status_bits(am, wl, oracle):
+    cap = 600
+    batch = wl.config_batched(B=6, k=7, V=8192, seed=91, cap=cap)
+    g = torch.Generator().manual_seed(2)
+    batch.state = wl.threshold_state(batch.B, cap, g, n_hist=cap - 3)      # three free slots: appends overflow
+    batch.draft_len = torch.tensor([7, 0, 3, 7, 5, 9], dtype=torch.int32)  # 9: out of range, clamped and flagged
+    batch.draft[2, 1, 5] = float("nan")
+    batch.draft_tokens[3, 2] = -4
+    oracle_len = batch.draft_len.clamp(0, 7)
+    a, st_a, _ = G.run_gpu(am, batch)
+    am.update_thresholds(st_a, batch.k, a.n_accept, a.H_q, a.d_js, draft_len=batch.draft_len.cuda(), status=a.status)
+    b, st_b, _ = G.run_gpu(am, batch, options=am.Options(apply_update=1))
+    torch.cuda.synchronize()
+    for name in ("n_accept", "next_token", "H_p", "H_q", "d_js", "p_accept", "accept_mask", "status"):
+        ga, gb = getattr(a, name), getattr(b, name)
+        assert torch.equal(torch.nan_to_num(ga.float(), nan=-7.0), torch.nan_to_num(gb.float(), nan=-7.0)), name
+    ha, hb = st_a.to_host(), st_b.to_host()
+    for k in ha:
+        assert np.array_equal(ha[k], hb[k]), k
+    st = b.status.cpu().numpy()
+    assert st[5] & am.binding.ST_BAD_LENGTH and st[2] & am.binding.ST_NONFINITE and st[3] & am.binding.ST_BAD_TOKEN
+    ref_batch = wl.VerifyBatch(batch.target, batch.draft, batch.draft_tokens, oracle_len, batch.state, batch.seed)
+    ref = G.run_oracle(oracle, ref_batch)
+    G.compare_verify(b, ref, info_bits=16 | 8 | am.binding.ST_BAD_LENGTH)
+    host = {k: np.array(v, copy=True) for k, v in batch.state.items() if k != "tau"}
+    oracle.update(host, ref["n_accept"], oracle_len.numpy(), ref["H_q"], ref["d_js"], batch.k, d_eps=1e-6)
+    for k in ("nA", "nR", "ent_cnt"):
+        assert np.array_equal(hb[k], host[k]), k
+
+
+def test_long_history_largest_window(am, wl, oracle):
+    cap = 2000
+    batch = wl.config_batched(B=2, k=64, V=4099, seed=6, cap=cap)
+    g = torch.Generator().manual_seed(4)
+    batch.state = wl.threshold_state(batch.B, cap, g, n_hist=1990)          # room for 10 in-loop appends
+    options = am.Options(list_update=1)
+    out, _, _ = G.run_gpu(am, batch, options=options)
+    ref = G.run_oracle(oracle, batch, options=options)
+    rep = G.compare_verify(out, ref)
+    _report("long history K=64", rep)
+
+
 # ------------------------------------------------------------------------------- close calls of the argmax
 @pytest.mark.parametrize("dtype,V", [(torch.bfloat16, 4104), (torch.float32, 2056), (torch.bfloat16, 4107)],
                          ids=["bf16-2slices", "f32-2slices", "bf16-unaligned"])
@@ -632,12 +698,17 @@ def test_verify_with_fused_update_matches_verify_then_update(am, wl, oracle):
         assert np.array_equal(hb[k], host[k]), k
 
 
-@pytest.mark.parametrize("literal", [False, True], ids=["default", "literal"])
-def test_closed_loop_rounds_against_oracle(am, wl, oracle, literal):
+@pytest.mark.parametrize("mode", ["default", "literal", "gen_only", "verify_only", "drawn_tokens"])
+def test_closed_loop_rounds_against_oracle(am, wl, oracle, mode):
     """Draft-entropy stop rule -> verify -> update for several rounds; the oracle runs its own
     trajectory and the GPU is fed the oracle's state each round (never the other way round).
-    literal: the verification loop as Algorithm 1 writes it, from the empty lists on."""
-    options = am.Options(base_test=1, list_update=1) if literal else am.Options()
+    literal: the verification loop as Algorithm 1 writes it, from the empty lists on.
+    gen_only / verify_only: the two ablations of Section 5.3 (adaptive window with plain speculative
+    sampling; fixed window of 5 with the adaptive acceptance test).
+    drawn_tokens: the drafted tokens come from adasd_draft_step (x_i ~ q_i) instead of the input source."""
+    options = {"literal": am.Options(base_test=1, list_update=1),
+               "gen_only": am.Options(relaxed_off=1)}.get(mode, am.Options())
+    fixed_window = 5 if mode == "verify_only" else 0
     from oracle import new_state
     B, V, W, cap, n_rounds = 4, 32000, 6, 256, 12
     src = wl.ClosedLoopSource(B, V, W, dtype=torch.bfloat16, seed=77)
@@ -655,16 +726,25 @@ def test_closed_loop_rounds_against_oracle(am, wl, oracle, literal):
         act_ref = np.ones(B, dtype=np.uint8)
         dl_ref = np.zeros(B, dtype=np.int32)
         dg = d.cuda()
+        tg_gpu, tg_ref, k_cap = (None, None, fixed_window) if fixed_window else (dev.T_G, host["T_G"], W)
         for step in range(W):
-            H, stop = am.draft_entropy(dg[:, step], ws, T_G=dev.T_G, active=active, step=step, k_max=W)
+            if mode == "drawn_tokens":
+                H, stop, x_gpu, _ = am.draft_step(dg[:, step], ws, T_G=tg_gpu, active=active, step=step, k_max=k_cap,
+                                                  seed=src.seed, round0=rnd)
+                x_ref, _ = oracle.draft_sample(d[:, step].contiguous(), active=act_ref, step=step, seed=src.seed,
+                                               round0=rnd)
+                assert np.array_equal(x_gpu.cpu().numpy(), x_ref)
+                x[:, step] = torch.tensor(np.maximum(x_ref, 0))        # (inactive rows keep a valid placeholder)
+            else:
+                H, stop = am.draft_entropy(dg[:, step], ws, T_G=tg_gpu, active=active, step=step, k_max=k_cap)
             dl_gpu += active.to(torch.int32)
             active = active & (1 - stop)
-            Href, sref = oracle.draft_entropy(d[:, step].contiguous(), T_G=host["T_G"], active=act_ref,
-                                              step=step, k_max=W)
+            Href, sref = oracle.draft_entropy(d[:, step].contiguous(), T_G=tg_ref, active=act_ref,
+                                              step=step, k_max=k_cap)
             dl_ref += act_ref
             # compare flags unless the entropy sits on the threshold
             live = act_ref.astype(bool)
-            near = np.abs(Href - host["T_G"]) < 1e-5 * np.abs(Href) + 1e-6
+            near = (np.abs(Href - host["T_G"]) < 1e-5 * np.abs(Href) + 1e-6) if not fixed_window else np.zeros(B, bool)
             assert G.close(H.cpu().numpy()[live], Href[live]).all()
             assert np.array_equal(stop.cpu().numpy()[live & ~near], sref[live & ~near])
             act_ref = act_ref & (1 - sref)
@@ -680,6 +760,8 @@ def test_closed_loop_rounds_against_oracle(am, wl, oracle, literal):
         ref = G.run_oracle(oracle, batch, options=options)
         rep = G.compare_verify(out, ref)
         total_flips += rep["flips"]
+        if mode == "gen_only":
+            assert (out.p_accept == 0).all() and ((out.accept_mask & 2) == 0).all()
         am.update_thresholds(dev, W, out.n_accept, out.H_q, out.d_js, draft_len=dl_gpu)
         got_before = dev.to_host()
         oracle.update(host, ref["n_accept"], dl_ref, ref["H_q"], ref["d_js"], W)
@@ -691,8 +773,11 @@ def test_closed_loop_rounds_against_oracle(am, wl, oracle, literal):
                                    rtol=1e-5, atol=1e-6)
     lens = np.array(lens)
     print(f"[closed loop] mean window {lens.mean():.2f}, flips {total_flips}, T_G {host['T_G']}", flush=True)
-    assert lens[0].max() == 1            # initial threshold 0: the first window has length 1
-    assert lens.max() > 1                # the threshold has adapted upwards since
+    if fixed_window:
+        assert (lens == fixed_window).all()
+    else:
+        assert lens[0].max() == 1            # initial threshold 0: the first window has length 1
+        assert lens.max() > 1                # the threshold has adapted upwards since
 
 
 def test_bounded_wait_expiry_gives_identical_results(am, wl):
