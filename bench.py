@@ -41,6 +41,9 @@ def main():
     ap.add_argument("--stats-path", type=int, default=0, help="0 library default, 1 two-kernel path, 2 single-read kernel")
     ap.add_argument("--separate-update", action="store_true",
                     help="apply the update step with a separate adasd_update_thresholds call")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step of each input set in a HIP graph once and time replays "
+                         "(the round counter then lives in device memory and is advanced inside the graph)")
     ap.add_argument("--literal", action="store_true",
                     help="time the variant that follows Algorithm 1's loop as written (options base_test=1, "
                          "list_update=1) instead of the default readings")
@@ -83,11 +86,36 @@ def main():
         torch.cuda.synchronize()
         print(f"calibration copy: {src.numel() * src.element_size()} bytes read and written", file=sys.stderr)
 
-    def step(i):
+    def eager_step(i, rounds=None):
         t, d, x, seed = sets[i % len(sets)]
-        am.verify(t, d, x, ws, state=state, seed=seed, round0=i, options=opts, out=out)
+        am.verify(t, d, x, ws, state=state, seed=seed, round0=i, rounds=rounds, options=opts, out=out)
         if args.separate_update:
             am.update_thresholds(state, K, out.n_accept, out.H_q, out.d_js)
+
+    step = eager_step
+    if args.graph:
+        rounds = torch.zeros(B, dtype=torch.int32, device="cuda")
+        one = torch.ones(B, dtype=torch.int32, device="cuda")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for i in range(len(sets)):
+                eager_step(i, rounds)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graphs = []
+        for i in range(len(sets)):
+            gph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gph):
+                eager_step(i, rounds)
+                rounds.add_(one)             # every replay, of whichever set, is one round later
+            graphs.append(gph)
+        state.load(host0.state)
+        rounds.zero_()
+        torch.cuda.synchronize()
+
+        def step(i):                         # noqa: F811
+            graphs[i % len(sets)].replay()
 
     for i in range(args.warmup):
         step(i)
@@ -109,7 +137,7 @@ def main():
     state.load(host0.state)
     torch.cuda.synchronize()
     for i in range(args.steps):
-        step(args.warmup + i)
+        eager_step(args.warmup + i)          # (kernel timing needs the launches themselves, not a replay)
     torch.cuda.synchronize()
     names = ["row_stats", "jsd", "decide", "sample", "update", "draft_entropy"]
     kern_us = {}
@@ -203,6 +231,7 @@ def main():
                                f"{len(sets)} rotating seeded input sets, history lists 64+64 per sequence",
                    "step": "adasd_verify + adasd_update_thresholds" if args.separate_update
                            else "adasd_verify with options.apply_update (update step in the decision kernel)",
+                   "launch": "replay of a captured HIP graph per input set" if args.graph else "eager launches",
                    "readings": "Algorithm 1's loop as written (base_test=1, list_update=1)" if args.literal
                                else "defaults (ratio test + residual, lists as of the round's start)"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -780,6 +780,69 @@ def test_closed_loop_rounds_against_oracle(am, wl, oracle, mode):
         assert lens.max() > 1                # the threshold has adapted upwards since
 
 
+def test_verify_and_draft_step_replay_from_a_hip_graph(am, wl):
+    """The library only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
+    memset), so a round can be captured once and replayed.  Every replay, with eager work and
+    synchronisations in between, must reproduce the eager results for the same round counter."""
+    batch = wl.config_batched(B=6, k=5, V=32000, seed=55, cap=640)
+    B, K, V = batch.B, batch.k, batch.V
+    t, d, x = batch.target.cuda(), batch.draft.cuda(), batch.draft_tokens.cuda()
+    ws = am.Workspace(B, K, V, torch.bfloat16)
+    st = am.State(B, 640).load(batch.state)
+    rounds = torch.zeros(B, dtype=torch.int32, device="cuda")
+    out = am.binding.alloc_verify_result(B, K)
+    H = torch.empty(B, dtype=torch.float32, device="cuda")
+    stop = torch.empty(B, dtype=torch.uint8, device="cuda")
+    tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    dst = torch.empty(B, dtype=torch.int32, device="cuda")
+    one = torch.ones(B, dtype=torch.int32, device="cuda")
+    opts = am.Options(apply_update=1)
+
+    def round_():
+        am.draft_step(d[:, 0], ws, T_G=st.T_G, step=0, k_max=K, seed=9, rounds=rounds, H_out=H, stop_out=stop,
+                      token_out=tok, status_out=dst)
+        am.verify(t, d, x, ws, state=st, seed=batch.seed, rounds=rounds, options=opts, out=out)
+        rounds.add_(one)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        r = {k: getattr(out, k).clone() for k in ("n_accept", "next_token", "H_q", "d_js", "p_accept", "status")}
+        r.update(H=H.clone(), stop=stop.clone(), tok=tok.clone(), state={k: torch.as_tensor(v).clone() for k, v in st.to_host().items()})
+        return r
+
+    eager = []
+    for _ in range(4):                                  # rounds 0..3 eagerly, from the initial state
+        round_()
+        eager.append(snapshot())
+    st.load(batch.state)
+    rounds.zero_()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up on the capture stream, then rewind
+        round_()
+    torch.cuda.current_stream().wait_stream(side)
+    st.load(batch.state)
+    rounds.zero_()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        round_()
+    st.load(batch.state)                                # capture does not run anything, but be explicit
+    rounds.zero_()
+    for i in range(4):
+        graph.replay()
+        got = snapshot()
+        junk = torch.randn(1 << 16, device="cuda").sum().item()      # eager work between replays
+        assert junk == junk
+        for k, v in eager[i].items():
+            if k == "state":
+                for name, ref in v.items():
+                    assert torch.equal(torch.nan_to_num(got["state"][name].double()), torch.nan_to_num(ref.double())), (i, name)
+            else:
+                assert torch.equal(torch.nan_to_num(got[k].double(), nan=-7.0), torch.nan_to_num(v.double(), nan=-7.0)), (i, k)
+
+
 def test_bounded_wait_expiry_gives_identical_results(am, wl):
     """With a spin limit of 0 every workgroup of the single-read kernel stops waiting at once and
     recomputes the other slices' results itself; the outputs must not change by a single bit."""
