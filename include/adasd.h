@@ -3,9 +3,11 @@
  * verification and threshold update of Adaptive Speculative Decoding (AdaSD).
  *
  * One decode round of Algorithm 1 of the paper, seen from this library:
- *   generation  : after every drafted token call adasd_draft_entropy on the draft
- *                 logits; it returns H(q_i) and the stop flag H(q_i) > T_G
- *                 (Section 4.3; generation loop of Algorithm 1);
+ *   generation  : for every drafting step call adasd_draft_step on the draft logits; it
+ *                 draws the token x_i ~ q_i and returns H(q_i) and the stop flag
+ *                 H(q_i) > T_G (Section 4.3; generation loop of Algorithm 1).  A
+ *                 caller with a sampler of its own calls adasd_draft_entropy instead,
+ *                 which leaves out the draw;
  *   verification: once the window is drafted call adasd_verify with the target and
  *                 draft logits of the k candidates (Sections 2.1.3, 2.2, 4.4;
  *                 verification loop of Algorithm 1);
@@ -252,8 +254,8 @@ int adasd_update_thresholds(const adasd_state *st /* host */, int k_max, const i
  * returns the summed duration and the number of kernels of one class since the last enable;
  * adasd_profile_disable frees the events.  Kernel classes: 0 row statistics (normalisers + entropy;
  * with stats_path 2 the single-read kernel and its finalisation, class 1 then stays empty),
- * 1 JS distance (two-kernel path), 2 decision, 3 token sampling, 4 state update, 5 draft entropy
- * (two kernels per call).
+ * 1 JS distance (two-kernel path), 2 decision, 3 token sampling, 4 state update, 5 drafting calls
+ * (adasd_draft_entropy and adasd_draft_step: two kernels per call).
  */
 int adasd_profile_enable(int max_launches);
 int adasd_profile_read(int kernel_class, double *total_ms /* host */, int *launches /* host */);
