@@ -82,10 +82,10 @@ size_t workspace_layout(size_t ws_bytes, Workspace* ws, void* base) {
       off = align_up(off + bytes, 256);
       return p + at;
     };
-    // arrival counters (the sampling kernel uses ticket3; the others are spare): fixed size, sized for the compiled limits
-    ws->ticket1 = reinterpret_cast<int32_t*>(take(65536 * sizeof(int32_t)));
-    ws->ticket2 = reinterpret_cast<int32_t*>(take(32768 * sizeof(int32_t)));
-    ws->ticket3 = reinterpret_cast<int32_t*>(take(32768 * sizeof(int32_t)));
+    // arrival counters: fixed size, sized for the compiled limits
+    ws->ticket1 = reinterpret_cast<int32_t*>(take(kTicket1Len * sizeof(int32_t)));
+    ws->ticket2 = reinterpret_cast<int32_t*>(take(kTicket2Len * sizeof(int32_t)));
+    ws->ticket3 = reinterpret_cast<int32_t*>(take(kTicket3Len * sizeof(int32_t)));
     ws->fused_cnt = reinterpret_cast<int32_t*>(take(cap * kRegionBytes[0]));
     ws->fused_slots = reinterpret_cast<uint64_t*>(take(cap * kRegionBytes[1]));
     ws->fused_norm = reinterpret_cast<uint64_t*>(take(cap * kRegionBytes[2]));
@@ -205,7 +205,7 @@ int adasd_draft_entropy(const void* draft_logits, adasd_dtype dt, int B, int V, 
   hipStream_t st = (hipStream_t)stream;
   const int S = pick_draft_split(B, V, (int)dt);
   Scope sc(5, st);
-  return launch_rowstats(map, (int)dt, B, S, ws, &dout, st) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
+  return launch_draft_step(map, (int)dt, S, ws, dout, nullptr, st) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
 }
 
 int adasd_draft_step(const void* draft_logits, adasd_dtype dt, int B, int V, int64_t row_stride,
@@ -241,7 +241,7 @@ int adasd_draft_step(const void* draft_logits, adasd_dtype dt, int B, int V, int
   hipStream_t st = (hipStream_t)stream;
   const int S = pick_draft_split(B, V, (int)dt);
   Scope sc(5, st);
-  return launch_draft_step(map, (int)dt, S, ws, dout, draw, st) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
+  return launch_draft_step(map, (int)dt, S, ws, dout, &draw, st) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
 }
 
 int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* stream) {
@@ -336,7 +336,7 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
     const int S = pick_split(rows, V, (int)a->dt);
     {
       Scope sc(0, st);
-      if (launch_rowstats(map, (int)a->dt, rows, S, ws, nullptr, st) != hipSuccess) return ADASD_ERR_HIP;
+      if (launch_rowstats(map, (int)a->dt, rows, S, ws, st) != hipSuccess) return ADASD_ERR_HIP;
     }
     {
       Scope sc(1, st);

@@ -647,7 +647,7 @@ __device__ void decide_position_wide(const DecideArgs& a, const UpdateArgs& upd,
     st_agent(reinterpret_cast<int*>(&dst->status), (int)rec.status);
     st_agent(&dst->d, rec.d);
     publish_barrier();
-    const int ticket = atomicAdd(&ws.ticket2[b], 1);
+    const int ticket = atomicAdd(&ws.ticket2[b * ticket_stride(a.map.B, kTicket2Len)], 1);
     wsh.last = ticket == K - 1;
   }
   __syncthreads();
@@ -693,7 +693,7 @@ __device__ void decide_position_wide(const DecideArgs& a, const UpdateArgs& upd,
     }
     ws.plan[b] = plan;
     a.status[b] = st_seq | st_all;
-    __hip_atomic_store(&ws.ticket2[b], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(&ws.ticket2[b * ticket_stride(a.map.B, kTicket2Len)], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   if (upd.B > 0) {
     publish_barrier();           // the status word above is read and OR-ed by another lane below

@@ -31,13 +31,13 @@ struct RowMap {
 
 struct Workspace {
   float4* part1;      // [rows][kMaxSplit]   (m, s, u, -) partial log-sum-exp states
-  int32_t* ticket1;   // [rows]              spare (zero)
+  int32_t* ticket1;   // [kTicket1Len]       arrival counters of the drafting kernel (row rho at rho * ticket_stride), zero between calls
   RowResult* rows;    // [rows]
   float2* part2;      // [positions][kMaxSplit] partial KL sums (p side, q side), log2 units
-  int32_t* ticket2;   // [positions]         spare (zero)
+  int32_t* ticket2;   // [kTicket2Len]       arrival counters of the long-history decision kernel, zero between calls
   SamplePlan* plan;   // [B]
   Top2* part3;        // [B][kMaxSampleSplit]
-  int32_t* ticket3;   // [B]                 arrival counters of the sampling kernel, zero between calls
+  int32_t* ticket3;   // [kTicket3Len]       arrival counters of the sampling kernel, zero between calls
   int32_t* fused_cnt; // [positions][kCntStride] arrival counters of the fused kernel, one per 128-byte line
   uint64_t* fused_slots; // [positions][kMaxFusedSplit][kSlotWords] self-validating hand-off words, zero between calls
   uint64_t* fused_norm;  // [positions][kSlotWords] folded triples of both rows, published by the position's leader
@@ -50,6 +50,14 @@ struct Workspace {
 // previous call left them zeroed.  Returns the number of positions the workspace can serve.
 size_t workspace_bytes_for(size_t positions);
 size_t workspace_layout(size_t ws_bytes, Workspace* ws, void* base);
+
+// Arrival counters of different rows / sequences sit on different 128-byte lines while the array is long
+// enough (read-modify-writes on one line are served one after the other, whatever word they hit).
+__host__ __device__ inline int ticket_stride(int count, int capacity) {
+  int st = count > 0 ? capacity / count : 32;
+  return st > 32 ? 32 : (st < 1 ? 1 : st);
+}
+constexpr int kTicket1Len = 65536, kTicket2Len = 32768, kTicket3Len = 32768;
 
 struct DraftOut {     // draft-entropy epilogue
   const float* T_G;
@@ -67,10 +75,10 @@ struct DraftDraw {    // token draw of a drafting step (x_i ~ q_i)
   int32_t* token_out;
   uint32_t* status;   // may be null
 };
-// One drafting step: entropy, stop flag and drawn token of each row (two kernels: scan, finish)
+// One drafting call: entropy and stop flag of each row, and with `draw` the drawn token (one kernel)
 int pick_draft_split(int rows, int V, int dt);
 hipError_t launch_draft_step(const RowMap& map, int dt, int S, const Workspace& ws, const DraftOut& dout,
-                             const DraftDraw& draw, hipStream_t st);
+                             const DraftDraw* draw /* or null */, hipStream_t st);
 
 struct VerifyOut {
   float* H_p;
@@ -93,9 +101,7 @@ inline void launch_kernel(Kernel kernel, dim3 grid, dim3 block, hipStream_t st, 
 
 int pick_split(int rows, int V, int dt);
 
-// dout: null in verify mode (the JS kernel folds the slice results), else the draft-entropy outputs
-hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Workspace& ws,
-                           const DraftOut* dout, hipStream_t st);
+hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Workspace& ws, hipStream_t st);
 bool fused_plan(const RowMap& map, int dt, int* NV_out, int* S_out);
 hipError_t launch_stats_fused(const RowMap& map, int dt, int NV, int S, int spin_limit,
                               const Workspace& ws, const VerifyOut& vout, hipStream_t st);

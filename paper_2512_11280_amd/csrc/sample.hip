@@ -132,7 +132,7 @@ __global__ void __launch_bounds__(kBlock, 6) k_sample(SampleArgs a, int S, Works
     st_agent(&dst->k1, t.k1); st_agent(&dst->i1, t.i1);
     st_agent(&dst->k2, t.k2); st_agent(&dst->i2, t.i2);
     publish_barrier();
-    int ticket = atomicAdd(&ws.ticket3[b], 1);
+    int ticket = atomicAdd(&ws.ticket3[b * ticket_stride(a.map.B, kTicket3Len)], 1);
     sh_mode = (ticket == S - 1) ? 1 : 0;
   }
   __syncthreads();
@@ -178,7 +178,7 @@ __global__ void __launch_bounds__(kBlock, 6) k_sample(SampleArgs a, int S, Works
       }
       if (mode == 1) a.next_token[b] = t.i1;
       sh_mode = mode;
-      __hip_atomic_store(&ws.ticket3[b], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&ws.ticket3[b * ticket_stride(a.map.B, kTicket3Len)], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
   __syncthreads();

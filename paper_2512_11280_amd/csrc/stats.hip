@@ -96,28 +96,6 @@ k_rowstats(RowMap map, int S, Workspace ws) {
   }
 }
 
-// Draft-entropy epilogue (stop rule of Algorithm 1's drafting loop): one wavefront per row.
-__global__ void __launch_bounds__(kBlock) k_rows_finish(RowMap map, int S, Workspace ws, DraftOut dout) {
-  const int lane = threadIdx.x & 63, rho = blockIdx.x * kWaves + (threadIdx.x >> 6);
-  if (rho >= map.B) return;
-  const bool active = map.active ? (map.active[rho] != 0) : true;
-  if (!active) {
-    if (lane == 0) {
-      dout.H_out[rho] = 0.f;
-      if (dout.stop_out) dout.stop_out[rho] = 0;
-    }
-    return;
-  }
-  const RowResult res = fold_row(ws, rho, S);
-  if (lane != 0) return;
-  ws.rows[rho] = res;
-  dout.H_out[rho] = res.H;
-  if (dout.stop_out) {
-    bool over = dout.T_G ? (res.H > dout.T_G[rho]) : false;
-    dout.stop_out[rho] = (uint8_t)(over || dout.force_stop || res.bad);
-  }
-}
-
 // ---------------------------------------------------------------------------------------------
 // Pass 2: JS divergence.  Per element, with b = max(p,q), r = min(p,q)/max(p,q) = 2^-|delta| and
 // delta = log2 q - log2 p,
@@ -248,8 +226,7 @@ static int pick_batch(int V, int dt, int S, int most) {
   return nb;
 }
 
-hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Workspace& ws,
-                           const DraftOut* dout, hipStream_t st) {
+hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Workspace& ws, hipStream_t st) {
   if (rows <= 0) return hipSuccess;
   dim3 grid(S, rows), block(kBlock);
   const int nb = pick_batch(map.V, dt, S, 8);
@@ -258,8 +235,6 @@ hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Wor
   ADASD_ROW_CASE(ADASD_BF16, 1) ADASD_ROW_CASE(ADASD_BF16, 2) ADASD_ROW_CASE(ADASD_BF16, 4) ADASD_ROW_CASE(ADASD_BF16, 8)
   ADASD_ROW_CASE(ADASD_F32, 1) ADASD_ROW_CASE(ADASD_F32, 2) ADASD_ROW_CASE(ADASD_F32, 4) ADASD_ROW_CASE(ADASD_F32, 8)
 #undef ADASD_ROW_CASE
-  if (dout)    // draft-entropy mode: rows are finalised by a second, small kernel
-    launch_kernel(k_rows_finish, dim3((rows + kWaves - 1) / kWaves), block, st, map, S, ws, *dout);
   return hipGetLastError();
 }
 
