@@ -255,7 +255,7 @@ int adasd_update_thresholds(const adasd_state *st /* host */, int k_max, const i
  * adasd_profile_disable frees the events.  Kernel classes: 0 row statistics (normalisers + entropy;
  * with stats_path 2 the single-read kernel and its finalisation, class 1 then stays empty),
  * 1 JS distance (two-kernel path), 2 decision, 3 token sampling, 4 state update, 5 drafting calls
- * (adasd_draft_entropy and adasd_draft_step: two kernels per call).
+ * (adasd_draft_entropy and adasd_draft_step: one kernel per call).
  */
 int adasd_profile_enable(int max_launches);
 int adasd_profile_read(int kernel_class, double *total_ms /* host */, int *launches /* host */);
