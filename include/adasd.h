@@ -232,6 +232,47 @@ int adasd_verify(const adasd_verify_args *args /* host */, const adasd_options *
                  void *stream);
 
 /*
+ * Column-sharded verification.  With a tensor-parallel output layer every holder g of G has the columns
+ * col_begin_g .. col_begin_g + V_g - 1 of every logit row.  The statistics of Appendix A and Section 2.2
+ * are sums over the vocabulary, so each holder forms partial results over its own columns and only small
+ * records travel (the caller moves them: on one device the G "holders" are G calls on column slices):
+ *
+ *   1. adasd_verify_shard_stats  (local)  -> triples_out  [rows][4]      rows = B*k_max*2, row 2*(b*k_max+i)
+ *        is the target row and the next one the draft row of position (b,i): (reference m, sum of
+ *        2^(z log2 e - m), sum of the same weighted by its exponent, 0) over the local columns;
+ *   2. gather the triples of all holders into triples_all [G][rows][4];
+ *      adasd_verify_shard_jsd    (local)  -> pos_out [B*k_max][4]: (partial Jensen-Shannon sum over the
+ *        local columns under the global normalisers, z_p(x), z_q(x), 1 if the drafted token x of the
+ *        position is a local column else 0);
+ *   3. gather into pos_all [G][B*k_max][4];
+ *      adasd_verify_shard_decide (replicated: every holder makes the same call and gets the same
+ *        results)                 -> everything adasd_verify writes except next_token: n_accept, H_p,
+ *        H_q, d_js, p_accept, accept_mask, status, and with options.apply_update the state.
+ *
+ * "local" calls take an adasd_verify_args whose V, logit pointers and strides describe the local column
+ * slice (outputs and state are not touched); the "replicated" call takes the whole-vocabulary V =
+ * shard->V_total, no logits, and the outputs.  All of a holder's calls of one round use the same
+ * workspace, in this order, on one stream.  Results agree with adasd_verify to the documented tolerance
+ * (the normalisers are folded from G partial sums instead of one launch's slices).  The holders' columns
+ * must tile 0 .. V_total-1; col_begin must be a multiple of 8; G <= ADASD_MAX_SHARDS.
+ */
+#define ADASD_MAX_SHARDS 64
+typedef struct {
+  int32_t n_shards;  /* G */
+  int32_t shard;     /* g: the holder whose columns a local call is given (ignored by replicated calls) */
+  int32_t V_total;   /* vocabulary size over all holders */
+  int32_t col_begin; /* first column of holder g (local calls) */
+} adasd_shard;
+
+int adasd_verify_shard_stats(const adasd_verify_args *local /* host */, const adasd_shard *shard /* host */,
+                             float *triples_out, void *stream);
+int adasd_verify_shard_jsd(const adasd_verify_args *local /* host */, const adasd_shard *shard /* host */,
+                           const float *triples_all, float *pos_out, void *stream);
+int adasd_verify_shard_decide(const adasd_verify_args *meta /* host */, const adasd_shard *shard /* host */,
+                              const float *triples_all, const float *pos_all,
+                              const adasd_options *opt /* host, may be NULL */, void *stream);
+
+/*
  * Update step (Section 4.3, Section 4.4 last paragraph; update lines of Algorithm 1).
  * For sequence b with r = n_accept[b]:
  *   every accepted position i < r : append d_js[b,i] to L_D^A unless it is "exactly 0 or 1";

@@ -54,6 +54,10 @@ class _VerifyArgs(C.Structure):
         ("workspace", C.c_void_p), ("ws_bytes", C.c_size_t)]
 
 
+class _Shard(C.Structure):
+    _fields_ = [("n_shards", C.c_int32), ("shard", C.c_int32), ("V_total", C.c_int32), ("col_begin", C.c_int32)]
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -80,6 +84,11 @@ def load_library():
                                       C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_size_t, C.c_void_p]
     L.adasd_verify.argtypes = [C.POINTER(_VerifyArgs), C.POINTER(_Options), C.c_void_p]
+    L.adasd_verify_shard_stats.argtypes = [C.POINTER(_VerifyArgs), C.POINTER(_Shard), C.c_void_p, C.c_void_p]
+    L.adasd_verify_shard_jsd.argtypes = [C.POINTER(_VerifyArgs), C.POINTER(_Shard), C.c_void_p, C.c_void_p,
+                                         C.c_void_p]
+    L.adasd_verify_shard_decide.argtypes = [C.POINTER(_VerifyArgs), C.POINTER(_Shard), C.c_void_p, C.c_void_p,
+                                            C.POINTER(_Options), C.c_void_p]
     L.adasd_update_thresholds.argtypes = [C.POINTER(_State), C.c_int, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.POINTER(_Options), C.c_void_p,
                                           C.c_void_p]
@@ -300,6 +309,94 @@ def verify(target_logits: torch.Tensor, draft_logits: torch.Tensor, draft_tokens
     opt = options._c() if options is not None else None
     rc = load_library().adasd_verify(C.byref(a), C.byref(opt) if opt is not None else None, _stream())
     _check(rc, "adasd_verify")
+    return out
+
+
+@dataclass
+class Shard:
+    """adasd_shard: which columns of the vocabulary a column-sharded call is given."""
+    n_shards: int
+    shard: int
+    V_total: int
+    col_begin: int
+
+    def _c(self) -> _Shard:
+        return _Shard(self.n_shards, self.shard, self.V_total, self.col_begin)
+
+
+def _local_args(target_local, draft_local, draft_tokens, workspace, draft_len, seed=0, seq_id=None, rounds=None,
+                round0=0, next_token=None, status=None) -> _VerifyArgs:
+    """adasd_verify_args of a local (column slice) call: logits and strides of the slice, no outputs."""
+    B, K1, V = target_local.shape
+    K = K1 - 1
+    if tuple(draft_local.shape) != (B, K, V) or target_local.stride(2) != 1 or (K > 0 and draft_local.stride(2) != 1):
+        raise ValueError("local logits must be [B, k(+1), V_local] with the vocabulary contiguous")
+    _need(draft_tokens, torch.int32, "draft_tokens")
+    _need(draft_len, torch.int32, "draft_len", optional=True)
+    _need(seq_id, torch.int32, "seq_id", optional=True)
+    _need(rounds, torch.int32, "rounds", optional=True)
+    return _VerifyArgs(
+        target_local.data_ptr(), draft_local.data_ptr(), _dtype_code(target_local), B, K, V,
+        target_local.stride(0), target_local.stride(1),
+        draft_local.stride(0) if K > 0 else V, draft_local.stride(1) if K > 0 else V,
+        draft_tokens.data_ptr(), _p(draft_len), None, seed & 0xFFFFFFFFFFFFFFFF, _p(seq_id), _p(rounds),
+        round0 & 0xFFFFFFFF, None, _p(next_token), None, None, None, None, None, _p(status),
+        workspace.ptr, workspace.bytes)
+
+
+def verify_shard_stats(target_local, draft_local, draft_tokens, workspace: Workspace, shard: Shard,
+                       draft_len=None, triples_out=None):
+    """adasd_verify_shard_stats: one (reference, sum, weighted sum) triple per row over the local columns."""
+    a = _local_args(target_local, draft_local, draft_tokens, workspace, draft_len)
+    if triples_out is None:
+        triples_out = torch.empty(a.B * a.k_max * 2, 4, dtype=torch.float32, device=target_local.device)
+    sh = shard._c()
+    _check(load_library().adasd_verify_shard_stats(C.byref(a), C.byref(sh), triples_out.data_ptr(), _stream()),
+           "adasd_verify_shard_stats")
+    return triples_out
+
+
+def verify_shard_jsd(target_local, draft_local, draft_tokens, workspace: Workspace, shard: Shard,
+                     triples_all: torch.Tensor, draft_len=None, pos_out=None):
+    """adasd_verify_shard_jsd: per position the local partial JS sum and the drafted token's logits."""
+    a = _local_args(target_local, draft_local, draft_tokens, workspace, draft_len)
+    _need(triples_all, torch.float32, "triples_all")
+    if pos_out is None:
+        pos_out = torch.empty(a.B * a.k_max, 4, dtype=torch.float32, device=target_local.device)
+    sh = shard._c()
+    _check(load_library().adasd_verify_shard_jsd(C.byref(a), C.byref(sh), triples_all.data_ptr(),
+                                                 pos_out.data_ptr(), _stream()), "adasd_verify_shard_jsd")
+    return pos_out
+
+
+def verify_shard_decide(B: int, k: int, dtype, draft_tokens, workspace: Workspace, shard: Shard,
+                        triples_all: torch.Tensor, pos_all: torch.Tensor, state: Optional[State] = None,
+                        draft_len=None, seed: int = 0, seq_id=None, rounds=None, round0: int = 0,
+                        options: Optional[Options] = None, out: Optional[VerifyResult] = None) -> VerifyResult:
+    """adasd_verify_shard_decide: the decisions of the round from the gathered records (no logits)."""
+    _need(draft_tokens, torch.int32, "draft_tokens")
+    _need(draft_len, torch.int32, "draft_len", optional=True)
+    _need(seq_id, torch.int32, "seq_id", optional=True)
+    _need(rounds, torch.int32, "rounds", optional=True)
+    _need(triples_all, torch.float32, "triples_all")
+    _need(pos_all, torch.float32, "pos_all")
+    if out is None:
+        out = alloc_verify_result(B, k, draft_tokens.device)
+    st = state._c() if state is not None else None
+    V = shard.V_total
+    a = _VerifyArgs(
+        None, None, BF16 if dtype == torch.bfloat16 else F32, B, k, V, (k + 1) * V, V, k * V, V,
+        draft_tokens.data_ptr(), _p(draft_len), C.pointer(st) if st is not None else None,
+        seed & 0xFFFFFFFFFFFFFFFF, _p(seq_id), _p(rounds), round0 & 0xFFFFFFFF,
+        out.n_accept.data_ptr(), out.next_token.data_ptr(), out.H_p.data_ptr(), out.H_q.data_ptr(),
+        out.d_js.data_ptr(), out.p_accept.data_ptr(), out.accept_mask.data_ptr(),
+        out.status.data_ptr(), workspace.ptr, workspace.bytes)
+    opt = options._c() if options is not None else None
+    sh = shard._c()
+    rc = load_library().adasd_verify_shard_decide(C.byref(a), C.byref(sh), triples_all.data_ptr(),
+                                                  pos_all.data_ptr(),
+                                                  C.byref(opt) if opt is not None else None, _stream())
+    _check(rc, "adasd_verify_shard_decide")
     return out
 
 

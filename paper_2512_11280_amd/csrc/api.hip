@@ -58,6 +58,7 @@ constexpr size_t kRegionBytes[] = {
     sizeof(SamplePlan),                                   // plan
     (size_t)kMaxSampleSplit * sizeof(Top2),               // part3
     sizeof(PosRecord),                                    // pos_rec
+    sizeof(float2),                                       // tok
 };
 constexpr size_t per_position_bytes() {
   size_t t = 0;
@@ -67,11 +68,11 @@ constexpr size_t per_position_bytes() {
 }  // namespace
 
 size_t workspace_bytes_for(size_t positions) {
-  return kHeaderBytes + (positions + 1) * per_position_bytes() + 9 * 256;
+  return kHeaderBytes + (positions + 1) * per_position_bytes() + 10 * 256;
 }
 
 size_t workspace_layout(size_t ws_bytes, Workspace* ws, void* base) {
-  const size_t slack = kHeaderBytes + 9 * 256;
+  const size_t slack = kHeaderBytes + 10 * 256;
   if (ws_bytes <= slack) return 0;
   const size_t cap = (ws_bytes - slack) / per_position_bytes();
   if (ws && cap > 0) {
@@ -95,6 +96,7 @@ size_t workspace_layout(size_t ws_bytes, Workspace* ws, void* base) {
     ws->plan = reinterpret_cast<SamplePlan*>(take(cap * kRegionBytes[6]));
     ws->part3 = reinterpret_cast<Top2*>(take(cap * kRegionBytes[7]));
     ws->pos_rec = reinterpret_cast<PosRecord*>(take(cap * kRegionBytes[8]));
+    ws->tok = reinterpret_cast<float2*>(take(cap * kRegionBytes[9]));
     ws->bytes = off;
   }
   return cap;
@@ -244,7 +246,20 @@ int adasd_draft_step(const void* draft_logits, adasd_dtype dt, int B, int V, int
   return launch_draft_step(map, (int)dt, S, ws, dout, &draw, st) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
 }
 
-int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* stream) {
+namespace {
+
+// Everything adasd_verify and the column-sharded entry points derive from their arguments.
+struct VerifySetup {
+  adasd_options opt;
+  Workspace ws;
+  RowMap map;
+  DecideArgs d;
+  UpdateArgs upd;
+};
+enum { kWantLogits = 1, kWantOutputs = 2, kWantToken = 4 };
+
+// Returns ADASD_OK with `out` filled, a negative error code, or 1 for an empty batch (nothing to do).
+int verify_setup(const adasd_verify_args* a, const adasd_options* opt_in, int wants, VerifySetup* out) {
   if (!a) return ADASD_ERR_INVALID_ARG;
   adasd_options opt{};
   if (opt_in) opt = *opt_in;
@@ -257,13 +272,18 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   if (opt.stats_path < 0 || opt.stats_path > 2) return ADASD_ERR_INVALID_ARG;
   if (opt.apply_update != 0 && opt.apply_update != 1) return ADASD_ERR_INVALID_ARG;
   if (opt.apply_update && !a->state) return ADASD_ERR_INVALID_ARG;
-  if (a->B == 0) return ADASD_OK;
+  if (a->B == 0) return 1;
   const int B = a->B, K = a->k_max, V = a->V;
-  if (!a->target_logits || !a->n_accept || !a->next_token || !a->status) return ADASD_ERR_INVALID_ARG;
-  if (K > 0 && (!a->draft_logits || !a->draft_tokens || !a->H_q || !a->d_js))
-    return ADASD_ERR_INVALID_ARG;
-  if (a->t_pos_stride < V || a->t_seq_stride < (int64_t)(K + 1) * V) return ADASD_ERR_INVALID_ARG;
-  if (K > 0 && (a->d_pos_stride < V || a->d_seq_stride < (int64_t)K * V)) return ADASD_ERR_INVALID_ARG;
+  if ((wants & kWantLogits) && !a->target_logits) return ADASD_ERR_INVALID_ARG;
+  if ((wants & kWantOutputs) && (!a->n_accept || !a->status)) return ADASD_ERR_INVALID_ARG;
+  if ((wants & kWantToken) && (!a->next_token || !a->status)) return ADASD_ERR_INVALID_ARG;
+  if (K > 0 && (wants & kWantLogits) && !a->draft_logits) return ADASD_ERR_INVALID_ARG;
+  if (K > 0 && !a->draft_tokens) return ADASD_ERR_INVALID_ARG;
+  if (K > 0 && (wants & kWantOutputs) && (!a->H_q || !a->d_js)) return ADASD_ERR_INVALID_ARG;
+  if (wants & kWantLogits) {
+    if (a->t_pos_stride < V || a->t_seq_stride < (int64_t)(K + 1) * V) return ADASD_ERR_INVALID_ARG;
+    if (K > 0 && (a->d_pos_stride < V || a->d_seq_stride < (int64_t)K * V)) return ADASD_ERR_INVALID_ARG;
+  }
   const size_t es = a->dt == ADASD_BF16 ? 2 : 4;
   if (!aligned_to(a->target_logits, es) || !aligned_to(a->draft_logits, es) ||
       !aligned_to(a->draft_tokens, 4) || !aligned_to(a->draft_len, 4) || !aligned_to(a->seq_id, 4) ||
@@ -282,7 +302,6 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   if (workspace_layout(a->ws_bytes, &ws, a->workspace) < (size_t)B * (size_t)(K > 0 ? K : 1))
     return ADASD_ERR_WORKSPACE;
 
-  hipStream_t st = (hipStream_t)stream;
   RowMap map{};
   map.base[0] = static_cast<const char*>(a->target_logits);
   map.base[1] = static_cast<const char*>(a->draft_logits);
@@ -326,6 +345,62 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   d.p_accept = a->p_accept;
   d.accept_mask = a->accept_mask;
   d.status = a->status;
+
+  UpdateArgs upd{};            // B = 0: the state is only read
+  if (opt.apply_update) {
+    upd = state_args(a->state);
+    upd.K = K;
+    upd.n_accept = a->n_accept;
+    upd.draft_len = a->draft_len;
+    upd.H_q = a->H_q;
+    upd.d_js = a->d_js;
+    upd.d_eps = d.d_eps;
+    upd.status = a->status;
+  }
+  out->opt = opt;
+  out->ws = ws;
+  out->map = map;
+  out->d = d;
+  out->upd = upd;
+  return ADASD_OK;
+}
+
+SampleArgs sample_args(const adasd_verify_args* a, const VerifySetup& v) {
+  SampleArgs s{};
+  s.map = v.map;
+  s.dt = (int)a->dt;
+  s.seed_lo = v.d.seed_lo;
+  s.seed_hi = v.d.seed_hi;
+  s.seq_id = a->seq_id;
+  s.round = a->round;
+  s.round0 = a->round0;
+  s.next_token = a->next_token;
+  s.status = a->status;
+  return s;
+}
+
+// about two 16-byte vectors per thread: enough workgroups to cover the chip for a handful of rows
+int sample_split(int V, int dt) {
+  const int nvec = V / (dt == ADASD_BF16 ? 8 : 4);
+  int S3 = (nvec + 2 * kBlock - 1) / (2 * kBlock);
+  if (S3 < 1) S3 = 1;
+  if (S3 > kMaxSampleSplit) S3 = kMaxSampleSplit;
+  return S3;
+}
+
+}  // namespace
+
+int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* stream) {
+  VerifySetup v;
+  int rc = verify_setup(a, opt_in, kWantLogits | kWantOutputs | kWantToken, &v);
+  if (rc) return rc < 0 ? rc : ADASD_OK;
+  const adasd_options& opt = v.opt;
+  const Workspace& ws = v.ws;
+  const RowMap& map = v.map;
+  DecideArgs& d = v.d;
+  const UpdateArgs& upd = v.upd;
+  const int B = a->B, K = a->k_max, V = a->V;
+  hipStream_t st = (hipStream_t)stream;
   VerifyOut vout{a->H_p, a->H_q, a->d_js};
   int fNV = 0, fS = 0;
   if (K > 0 && opt.stats_path == 2 && fused_plan(map, (int)a->dt, &fNV, &fS)) {
@@ -340,45 +415,101 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
     }
     {
       Scope sc(1, st);
-      if (launch_jsd(map, (int)a->dt, S, ws, vout, st) != hipSuccess) return ADASD_ERR_HIP;
+      if (launch_jsd(map, (int)a->dt, S, S, ws, vout, st) != hipSuccess) return ADASD_ERR_HIP;
     }
     d.jsd_split = S;
-  }
-  UpdateArgs upd{};            // B = 0: the state is only read
-  if (opt.apply_update) {
-    upd = state_args(a->state);
-    upd.K = K;
-    upd.n_accept = a->n_accept;
-    upd.draft_len = a->draft_len;
-    upd.H_q = a->H_q;
-    upd.d_js = a->d_js;
-    upd.d_eps = d.d_eps;
-    upd.status = a->status;
   }
   {
     Scope sc(2, st);
     if (launch_decide(d, upd, ws, st) != hipSuccess) return ADASD_ERR_HIP;
   }
 
-  SampleArgs s{};
-  s.map = map;
-  s.dt = (int)a->dt;
-  s.seed_lo = d.seed_lo;
-  s.seed_hi = d.seed_hi;
-  s.seq_id = a->seq_id;
-  s.round = a->round;
-  s.round0 = a->round0;
-  s.next_token = a->next_token;
-  s.status = a->status;
-  // about two 16-byte vectors per thread: enough workgroups to cover the chip for a handful of rows
-  const int nvec = V / ((int)a->dt == ADASD_BF16 ? 8 : 4);
-  int S3 = (nvec + 2 * kBlock - 1) / (2 * kBlock);
-  if (S3 < 1) S3 = 1;
-  if (S3 > kMaxSampleSplit) S3 = kMaxSampleSplit;
+  const SampleArgs s = sample_args(a, v);
+  const int S3 = sample_split(V, (int)a->dt);
   {
     Scope sc(3, st);
     if (launch_sample(s, S3, ws, st) != hipSuccess) return ADASD_ERR_HIP;
   }
+  return ADASD_OK;
+}
+
+// ---- column-sharded verification ---------------------------------------------------------------
+static int check_shard(const adasd_shard* sh, int V_local, bool local) {
+  if (!sh) return ADASD_ERR_INVALID_ARG;
+  if (sh->n_shards < 1 || sh->n_shards > ADASD_MAX_SHARDS) return ADASD_ERR_CAPACITY;
+  if (sh->V_total < 1 || sh->V_total > ADASD_MAX_V) return ADASD_ERR_CAPACITY;
+  if (!local) return V_local == sh->V_total ? ADASD_OK : ADASD_ERR_INVALID_ARG;
+  if (sh->shard < 0 || sh->shard >= sh->n_shards) return ADASD_ERR_INVALID_ARG;
+  if (sh->col_begin < 0 || (sh->col_begin & 7) || (int64_t)sh->col_begin + V_local > sh->V_total)
+    return ADASD_ERR_INVALID_ARG;
+  return ADASD_OK;
+}
+
+int adasd_verify_shard_stats(const adasd_verify_args* local, const adasd_shard* sh, float* triples_out, void* stream) {
+  VerifySetup v;
+  int rc = verify_setup(local, nullptr, kWantLogits, &v);
+  if (rc) return rc < 0 ? rc : ADASD_OK;
+  rc = check_shard(sh, local->V, true);
+  if (rc) return rc;
+  const int rows = local->B * local->k_max * 2;
+  if (rows == 0) return ADASD_OK;
+  if (!triples_out) return ADASD_ERR_INVALID_ARG;
+  if (!aligned_to(triples_out, 16)) return ADASD_ERR_MISALIGNED;
+  hipStream_t st = (hipStream_t)stream;
+  const int S = pick_split(rows, local->V, (int)local->dt);
+  Scope sc(0, st);
+  if (launch_rowstats(v.map, (int)local->dt, rows, S, v.ws, st) != hipSuccess) return ADASD_ERR_HIP;
+  if (launch_shard_fold_rows(v.map, S, v.ws, reinterpret_cast<float4*>(triples_out), st) != hipSuccess) return ADASD_ERR_HIP;
+  return ADASD_OK;
+}
+
+int adasd_verify_shard_jsd(const adasd_verify_args* local, const adasd_shard* sh, const float* triples_all,
+                           float* pos_out, void* stream) {
+  VerifySetup v;
+  int rc = verify_setup(local, nullptr, kWantLogits, &v);
+  if (rc) return rc < 0 ? rc : ADASD_OK;
+  rc = check_shard(sh, local->V, true);
+  if (rc) return rc;
+  const int rows = local->B * local->k_max * 2;
+  if (rows == 0) return ADASD_OK;
+  if (!triples_all || !pos_out) return ADASD_ERR_INVALID_ARG;
+  if (!aligned_to(triples_all, 16) || !aligned_to(pos_out, 16)) return ADASD_ERR_MISALIGNED;
+  hipStream_t st = (hipStream_t)stream;
+  const int S = pick_split(rows, local->V, (int)local->dt);
+  Scope sc(1, st);
+  if (launch_shard_scatter_rows(reinterpret_cast<const float4*>(triples_all), sh->n_shards, rows, v.ws, st) != hipSuccess)
+    return ADASD_ERR_HIP;
+  const VerifyOut none{nullptr, nullptr, nullptr};
+  if (launch_jsd(v.map, (int)local->dt, S, sh->n_shards, v.ws, none, st) != hipSuccess) return ADASD_ERR_HIP;
+  if (launch_shard_fold_pos(v.map, (int)local->dt, S, v.ws, local->draft_tokens, sh->col_begin,
+                            reinterpret_cast<float4*>(pos_out), st) != hipSuccess)
+    return ADASD_ERR_HIP;
+  return ADASD_OK;
+}
+
+int adasd_verify_shard_decide(const adasd_verify_args* meta, const adasd_shard* sh, const float* triples_all,
+                              const float* pos_all, const adasd_options* opt, void* stream) {
+  VerifySetup v;
+  int rc = verify_setup(meta, opt, kWantOutputs, &v);
+  if (rc) return rc < 0 ? rc : ADASD_OK;
+  rc = check_shard(sh, meta->V, false);
+  if (rc) return rc;
+  const int rows = meta->B * meta->k_max * 2;
+  if (rows > 0 && (!triples_all || !pos_all)) return ADASD_ERR_INVALID_ARG;
+  if (!aligned_to(triples_all, 16) || !aligned_to(pos_all, 16)) return ADASD_ERR_MISALIGNED;
+  hipStream_t st = (hipStream_t)stream;
+  Scope sc(2, st);
+  if (rows > 0) {
+    if (launch_shard_scatter_rows(reinterpret_cast<const float4*>(triples_all), sh->n_shards, rows, v.ws, st) != hipSuccess)
+      return ADASD_ERR_HIP;
+    if (launch_shard_prepare(v.map, reinterpret_cast<const float4*>(pos_all), sh->n_shards, v.ws, meta->H_p, meta->H_q,
+                             st) != hipSuccess)
+      return ADASD_ERR_HIP;
+    v.d.jsd_split = sh->n_shards;
+    v.d.tok = v.ws.tok;
+  }
+  v.d.map.base[0] = v.d.map.base[1] = nullptr;      // no logits in this call
+  if (launch_decide(v.d, v.upd, v.ws, st) != hipSuccess) return ADASD_ERR_HIP;
   return ADASD_OK;
 }
 

@@ -119,8 +119,14 @@ __device__ __forceinline__ PosLoad load_position(const DecideArgs& a, const Work
       ((int64_t)b * a.map.seq_stride[0] + (int64_t)i * a.map.pos_stride[0]) * Elem<DT>::bytes;
   const char* qrow = a.map.base[1] +
       ((int64_t)b * a.map.seq_stride[1] + (int64_t)i * a.map.pos_stride[1]) * Elem<DT>::bytes;
-  L.zp = load_elem<DT>(prow, L.x_ok ? L.x : 0);
-  L.zq = load_elem<DT>(qrow, L.x_ok ? L.x : 0);
+  if (a.tok) {            // column-sharded call: the owning shard looked the two logits up
+    const float2 z = a.tok[o];
+    L.zp = z.x;
+    L.zq = z.y;
+  } else {
+    L.zp = load_elem<DT>(prow, L.x_ok ? L.x : 0);
+    L.zq = load_elem<DT>(qrow, L.x_ok ? L.x : 0);
+  }
   L.rp = ws.rows[2 * o];
   L.rq = ws.rows[2 * o + 1];
   L.p0 = L.p1 = 0.f;

@@ -42,6 +42,7 @@ struct Workspace {
   uint64_t* fused_slots; // [positions][kMaxFusedSplit][kSlotWords] self-validating hand-off words, zero between calls
   uint64_t* fused_norm;  // [positions][kSlotWords] folded triples of both rows, published by the position's leader
   PosRecord* pos_rec; // [positions] outcomes of the positions (long-history decision kernel)
+  float2* tok;        // [positions] logits of the drafted tokens gathered from the column shards
   size_t bytes;
 };
 
@@ -138,6 +139,7 @@ struct DecideArgs {
   const uint32_t* round;
   uint32_t round0;
   int32_t reject_rule, kde_min_n, bw_rule, relaxed_off;
+  const float2* tok;    // non-null: (z_p(x), z_q(x)) of every position's drafted token; the logits are then not read
   int32_t base_test;    // 1: match test of the verification loop, replacement from p without the drafted token
   int32_t list_update;  // 1: the accepted list grows inside the loop
   float d_eps;          // filter of the in-loop appends
@@ -153,8 +155,17 @@ struct DecideArgs {
 // upd.B > 0: the round is also applied to the state (the update step) by the same kernel
 hipError_t launch_decide(const DecideArgs& a, const UpdateArgs& upd, const Workspace& ws, hipStream_t st);
 // JS distance: per-slice partial sums (the decision kernel adds them up), rows and entropies
-hipError_t launch_jsd(const RowMap& map, int dt, int S, const Workspace& ws, const VerifyOut& vout,
+// S_fold: slice records per row that the kernel folds into the normalisers (S for a whole-vocabulary call)
+hipError_t launch_jsd(const RowMap& map, int dt, int S, int S_fold, const Workspace& ws, const VerifyOut& vout,
                       hipStream_t st);
+
+// ---- column-sharded verification: records exchanged between the shards (float4 each)
+hipError_t launch_shard_fold_rows(const RowMap& map, int S, const Workspace& ws, float4* triples_out, hipStream_t st);
+hipError_t launch_shard_scatter_rows(const float4* triples_all, int G, int rows, const Workspace& ws, hipStream_t st);
+hipError_t launch_shard_fold_pos(const RowMap& map, int dt, int S, const Workspace& ws, const int32_t* draft_tokens,
+                                 int col_begin, float4* pos_out, hipStream_t st);
+hipError_t launch_shard_prepare(const RowMap& map, const float4* pos_all, int G, const Workspace& ws, float* H_p,
+                                float* H_q, hipStream_t st);
 
 struct SampleArgs {
   RowMap map;

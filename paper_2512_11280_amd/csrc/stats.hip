@@ -117,8 +117,8 @@ __device__ __forceinline__ void jsd_push(float zp, float zq, float cp, float cq,
 
 template <int DT, int kJsdBatch>   // kJsdBatch: vector pairs per thread and batch
 __global__ void __launch_bounds__(kBlock)
-k_jsd(RowMap map, int S, Workspace ws, VerifyOut vout) {
-  warm_kernargs<sizeof(RowMap) + sizeof(int) + sizeof(Workspace) + sizeof(VerifyOut)>();
+k_jsd(RowMap map, int S, int S_fold, Workspace ws, VerifyOut vout) {
+  warm_kernargs<sizeof(RowMap) + 2 * sizeof(int) + sizeof(Workspace) + sizeof(VerifyOut)>();
   constexpr int EPV = Elem<DT>::per_vec;
   const int pos = blockIdx.y, s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   __shared__ RowResult sh_row[2];
@@ -149,7 +149,7 @@ k_jsd(RowMap map, int S, Workspace ws, VerifyOut vout) {
 
   // both rows' slice results are folded by every workgroup of the position, the same way
   if (wave < 2) {
-    const RowResult res = fold_row(ws, 2 * pos + wave, S);
+    const RowResult res = fold_row(ws, 2 * pos + wave, S_fold);   // S_fold records per row: this call's slices, or one per column shard
     if (lane == 0) sh_row[wave] = res;
   }
   __syncthreads();
@@ -199,7 +199,7 @@ k_jsd(RowMap map, int S, Workspace ws, VerifyOut vout) {
       ws.rows[2 * pos] = resp;
       ws.rows[2 * pos + 1] = resq;
       if (vout.H_p) vout.H_p[pos] = resp.H;
-      vout.H_q[pos] = resq.H;
+      if (vout.H_q) vout.H_q[pos] = resq.H;
     }
   }
 }
@@ -238,14 +238,14 @@ hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Wor
   return hipGetLastError();
 }
 
-hipError_t launch_jsd(const RowMap& map, int dt, int S, const Workspace& ws, const VerifyOut& vout,
+hipError_t launch_jsd(const RowMap& map, int dt, int S, int S_fold, const Workspace& ws, const VerifyOut& vout,
                       hipStream_t st) {
   const int positions = map.B * map.K;
   if (positions <= 0) return hipSuccess;
   dim3 grid(S, positions), block(kBlock);
   const int nb = pick_batch(map.V, dt, S, 4);
 #define ADASD_JSD_CASE(DTV, NB) \
-  if (dt == DTV && nb == NB) launch_kernel((k_jsd<DTV, NB>), grid, block, st, map, S, ws, vout);
+  if (dt == DTV && nb == NB) launch_kernel((k_jsd<DTV, NB>), grid, block, st, map, S, S_fold, ws, vout);
   ADASD_JSD_CASE(ADASD_BF16, 1) ADASD_JSD_CASE(ADASD_BF16, 2) ADASD_JSD_CASE(ADASD_BF16, 4)
   ADASD_JSD_CASE(ADASD_F32, 1) ADASD_JSD_CASE(ADASD_F32, 2) ADASD_JSD_CASE(ADASD_F32, 4)
 #undef ADASD_JSD_CASE

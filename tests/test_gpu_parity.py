@@ -390,6 +390,87 @@ def test_long_history_largest_window(am, wl, oracle):
     _report("long history K=64", rep)
 
 
+# ------------------------------------------------------------------------------- column-sharded verification
+def _column_cuts(V, G):
+    """G column ranges that tile [0, V): starts are multiples of 8, sizes deliberately uneven."""
+    cuts = [0]
+    for g in range(1, G):
+        c = (V * g // G) // 8 * 8 + (8 if g % 2 else 0)
+        cuts.append(min(max(c, cuts[-1] + 8), V - 8 * (G - g)))
+    return cuts + [V]
+
+
+def _sharded_decisions(am, batch, n_sh, options=None, seq_id=None):
+    """Stages 1-3 of the column-sharded path on one device: G calls on column slices per stage."""
+    B, K, V = batch.B, batch.k, batch.V
+    t, d, x = batch.target.cuda(), batch.draft.cuda(), batch.draft_tokens.cuda()
+    dl = G.to_dev(batch.draft_len)
+    cuts = _column_cuts(V, n_sh)
+    wss = [am.Workspace(B, max(K, 1), V, batch.target.dtype) for _ in range(n_sh)]      # one per holder
+    shards = [am.Shard(n_sh, g, V, cuts[g]) for g in range(n_sh)]
+    views = [(t[:, :, cuts[g]:cuts[g + 1]], d[:, :, cuts[g]:cuts[g + 1]]) for g in range(n_sh)]
+    rows, P = B * K * 2, B * K
+    triples_all = torch.empty(n_sh, rows, 4, device="cuda")
+    pos_all = torch.empty(n_sh, P, 4, device="cuda")
+    for g in range(n_sh):
+        am.verify_shard_stats(views[g][0], views[g][1], x, wss[g], shards[g], draft_len=dl, triples_out=triples_all[g])
+    for g in range(n_sh):
+        am.verify_shard_jsd(views[g][0], views[g][1], x, wss[g], shards[g], triples_all, draft_len=dl, pos_out=pos_all[g])
+    cap = batch.state["LA"].shape[1]
+    outs, states = [], []
+    sid = None if seq_id is None else torch.tensor(np.asarray(seq_id, dtype=np.uint32).view(np.int32)).cuda()
+    for g in range(n_sh):                                # replicated: every holder must get the same
+        st = G.state_to_device(am, batch.state, B, cap)
+        outs.append(am.verify_shard_decide(B, K, batch.target.dtype, x, wss[g], shards[g], triples_all, pos_all,
+                                           state=st, draft_len=dl, seed=batch.seed, seq_id=sid,
+                                           round0=batch.round0, options=options))
+        states.append(st)
+    torch.cuda.synchronize()
+    return outs, states, wss, shards, views, (triples_all, pos_all)
+
+
+@pytest.mark.parametrize("G_", [1, 2, 5, 8])
+@pytest.mark.parametrize("opt", [dict(), dict(base_test=1, list_update=1), dict(apply_update=1)],
+                         ids=["default", "literal", "update"])
+def test_column_sharded_statistics_and_decisions(am, wl, oracle, G_, opt):
+    batch = wl.config_batched(B=5, k=6, V=32000, seed=400 + G_, cap=96)
+    batch.draft_len = torch.tensor([6, 0, 3, 6, 5], dtype=torch.int32)
+    batch.draft_tokens[3, 1] = 32000 + 5                       # out of range: no holder owns it
+    batch.draft[2, 1, 31999] = float("nan")                    # broken row, seen by the last holder only
+    options = am.Options(**opt)
+    outs, states, *_ = _sharded_decisions(am, batch, G_, options=options)
+    ref = G.run_oracle(oracle, batch, options=options)
+    names = ("n_accept", "H_p", "H_q", "d_js", "p_accept", "accept_mask", "status")
+    for o in outs[1:]:                                         # the replicas agree bit for bit
+        for n in names:
+            assert torch.equal(torch.nan_to_num(getattr(o, n).float(), nan=-7.0),
+                               torch.nan_to_num(getattr(outs[0], n).float(), nan=-7.0)), n
+    got = outs[0]
+    got.next_token = torch.tensor(ref["next_token"], dtype=torch.int32).cuda()      # (not produced by this stage)
+    sampled_bits = am.binding.ST_ZERO_MASS | am.binding.ST_EXACT_PATH
+    ref_status = ref["status"].copy()
+    ref["status"] = ref_status & ~np.uint32(sampled_bits)      # bits that only the sampling stage sets
+    rep = G.compare_verify(got, ref, info_bits=16 | 8)
+    _report(f"sharded G={G_} {opt}", rep)
+    assert rep["flips"] == 0
+    if opt.get("apply_update"):
+        host = {k: np.array(v, copy=True) for k, v in batch.state.items() if k != "tau"}
+        oracle.update(host, ref["n_accept"], batch.draft_len.numpy(), ref["H_q"], ref["d_js"], batch.k, d_eps=1e-6)
+        hb = states[0].to_host()
+        for k in ("nA", "nR", "ent_cnt"):
+            assert np.array_equal(hb[k], host[k]), k
+
+
+def test_column_sharded_argument_errors(am):
+    ws = am.Workspace(2, 2, 64, torch.float32)
+    t = torch.zeros(2, 3, 64, device="cuda")
+    d = torch.zeros(2, 2, 64, device="cuda")
+    tok = torch.zeros(2, 2, dtype=torch.int32, device="cuda")
+    for bad in (am.Shard(2, 2, 64, 0), am.Shard(2, 1, 64, 4), am.Shard(2, 1, 64, 32), am.Shard(65, 0, 64, 0)):
+        with pytest.raises(am.AdasdError):
+            am.verify_shard_stats(t[:, :, :40], d[:, :, :40], tok, ws, bad)
+
+
 # ------------------------------------------------------------------------------- close calls of the argmax
 @pytest.mark.parametrize("dtype,V", [(torch.bfloat16, 4104), (torch.float32, 2056), (torch.bfloat16, 4107)],
                          ids=["bf16-2slices", "f32-2slices", "bf16-unaligned"])
