@@ -44,6 +44,10 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture the step of each input set in a HIP graph once and time replays "
                          "(the round counter then lives in device memory and is advanced inside the graph)")
+    ap.add_argument("--shards", type=int, default=0,
+                    help="also time one holder's calls of the column-sharded path with this many holders "
+                         "(its V/G columns of the same workload; the other holders' records are computed "
+                         "beforehand), reported under 'sharded'")
     ap.add_argument("--literal", action="store_true",
                     help="time the variant that follows Algorithm 1's loop as written (options base_test=1, "
                          "list_update=1) instead of the default readings")
@@ -196,6 +200,46 @@ def main():
     draft_step_kernels_us = ms / 200 * 1e3 if n else None
     am.profile_disable()
 
+    # ---- one holder's share of the column-sharded path (its V/G columns, the replicated stages in full)
+    sharded = None
+    if args.shards > 0:
+        n_sh = args.shards
+        cuts = [V * g // n_sh // 8 * 8 for g in range(n_sh)] + [V]
+        t, d, x, seed = sets[0]
+        shards = [am.Shard(n_sh, g, V, cuts[g]) for g in range(n_sh)]
+        views = [(t[:, :, cuts[g]:cuts[g + 1]], d[:, :, cuts[g]:cuts[g + 1]]) for g in range(n_sh)]
+        tri = torch.empty(n_sh, B * K * 2, 4, device="cuda")
+        pos = torch.empty(n_sh, B * K, 4, device="cuda")
+        top = torch.empty(n_sh, B, 4, device="cuda")
+        cand = torch.empty(n_sh, B, am.binding.SHARD_CAND_BYTES, dtype=torch.uint8, device="cuda")
+        tau = torch.empty(B, dtype=torch.float32, device="cuda")
+        state.load(host0.state)
+
+        def holder(g, r):
+            """The calls holder g makes in one round, in order (the gathers between them are the caller's)."""
+            am.verify_shard_stats(views[g][0], views[g][1], x, ws, shards[g], triples_out=tri[g])
+            am.verify_shard_jsd(views[g][0], views[g][1], x, ws, shards[g], tri, pos_out=pos[g])
+            am.verify_shard_decide(B, K, torch.bfloat16, x, ws, shards[g], tri, pos, state=state, seed=seed,
+                                   round0=r, options=am.Options(apply_update=1), out=out)
+            am.verify_shard_sample(views[g][0], views[g][1], x, ws, shards[g], seed=seed, round0=r, top_out=top[g])
+            am.verify_shard_pick(B, K, torch.bfloat16, x, ws, shards[g], top, out, tau_out=tau)
+            am.verify_shard_refine(views[g][0], views[g][1], x, ws, shards[g], tau, seed=seed, round0=r,
+                                   cand_out=cand[g])
+            am.verify_shard_settle(B, K, torch.bfloat16, x, ws, shards[g], tau, cand, out, seed=seed, round0=r)
+
+        for g in range(n_sh):                 # fill every holder's records once
+            holder(g, 0)
+        torch.cuda.synchronize()
+        reps = 100
+        t1 = time.perf_counter()
+        for r in range(reps):
+            holder(0, r)
+        torch.cuda.synchronize()
+        sharded = {"holders": n_sh, "columns_per_holder": cuts[1] - cuts[0],
+                   "us_per_round_one_holder": (time.perf_counter() - t1) / reps * 1e6,
+                   "exchange_bytes_per_holder": (B * K * 2 + B * K + B) * 16 + B * am.binding.SHARD_CAND_BYTES}
+        state.load(host0.state)
+
     # ---- CPU oracle on the same workload (baseline, not a target)
     cpu = None
     if not args.no_cpu_baseline:
@@ -247,6 +291,7 @@ def main():
         "draft_step_us_per_call": draft_step_us,
         "draft_step_kernels_us": draft_step_kernels_us,
         "mean_accepted_length": mean_accept,
+        "sharded": sharded,
     }
     print(json.dumps(line))
 

@@ -64,7 +64,10 @@ enum {
   ADASD_ST_ZERO_MASS = 4u,   /* max(0, p - q) had no mass at the rejected position: token drawn from p */
   ADASD_ST_OVERFLOW = 8u,    /* a history list was full: the append was dropped */
   ADASD_ST_EXACT_PATH = 16u, /* informational: the float64 tie-resolution path chose the token */
-  ADASD_ST_BAD_LENGTH = 32u  /* draft_len[b] outside [0,k_max]: clamped */
+  ADASD_ST_BAD_LENGTH = 32u, /* draft_len[b] outside [0,k_max]: clamped */
+  ADASD_ST_UNSETTLED = 64u   /* column-sharded sampling only: the draw could not be settled from the exchanged
+                                records (no element with certain mass, too many close candidates, or error
+                                bounds that overlap); next_token is the provisional winner or -1 */
 };
 
 /* Compiled limits. */
@@ -271,6 +274,45 @@ int adasd_verify_shard_jsd(const adasd_verify_args *local /* host */, const adas
 int adasd_verify_shard_decide(const adasd_verify_args *meta /* host */, const adasd_shard *shard /* host */,
                               const float *triples_all, const float *pos_all,
                               const adasd_options *opt /* host, may be NULL */, void *stream);
+
+/*
+ * Column-sharded sampling of the correction / bonus token (Section 2.1.3; last lines of the verification
+ * step of Algorithm 1), after adasd_verify_shard_decide on the same workspace (it leaves the row, the
+ * kind of draw and the normalisers of every sequence there).  The Gumbel noise of an element depends on
+ * its vocabulary index only, so the holders' draws are those of adasd_verify.
+ *
+ *   4. adasd_verify_shard_sample (local)      -> top_out [B][4]: (best upper-bound key over the local
+ *        columns, its vocabulary index as an int32 bit pattern (-1 none, -2 NaN/+inf in the row), the
+ *        runner-up key, the margin by which the best's true key may lie below its bound);
+ *   5. gather into top_all [G][B][4];
+ *      adasd_verify_shard_pick   (replicated) -> next_token [B] where the winner is certain; tau_out [B]
+ *        = +inf for those, else the key a candidate must reach (next_token then holds the provisional
+ *        winner);
+ *   6. adasd_verify_shard_refine (local)      -> cand_out [B] records of ADASD_SHARD_CAND_BYTES: for the
+ *        open sequences the local elements that reach tau (vocabulary index and logits, at most 8) and
+ *        the refined normaliser sums of the local columns;
+ *   7. gather into cand_all [G][B];
+ *      adasd_verify_shard_settle (replicated) -> next_token of the open sequences from float64 keys, with
+ *        ADASD_ST_EXACT_PATH, and tau = +inf for them; where the error bounds of the normalisers still
+ *        overlap, ADASD_ST_UNSETTLED is set, the provisional token stays and tau stays finite;
+ *   8. steps 6 and 7 once more with exact_sums = 1 (every term of the normaliser sums in float64, about
+ *        a millisecond per open sequence and holder at V = 128256) close those: the settle call clears
+ *        ADASD_ST_UNSETTLED when it succeeds.  What stays flagged has no sharded form: no element with
+ *        certain mass (e.g. identical target and draft rows: adasd_verify then draws from the target row
+ *        in float64 over the whole row) or more than 8 close candidates in one holder.
+ * Steps 6 to 8 do nothing for sequences that are settled (about 1.7e-4 of the draws are open after step 5).
+ * Local calls use args->seed, seq_id, round, round0; replicated calls write args->next_token and
+ * args->status (bits are OR-ed into what adasd_verify_shard_decide wrote).
+ */
+#define ADASD_SHARD_CAND_BYTES 128
+int adasd_verify_shard_sample(const adasd_verify_args *local /* host */, const adasd_shard *shard /* host */,
+                              float *top_out, void *stream);
+int adasd_verify_shard_pick(const adasd_verify_args *meta /* host */, const adasd_shard *shard /* host */,
+                            const float *top_all, float *tau_out, void *stream);
+int adasd_verify_shard_refine(const adasd_verify_args *local /* host */, const adasd_shard *shard /* host */,
+                              const float *tau, int exact_sums, void *cand_out, void *stream);
+int adasd_verify_shard_settle(const adasd_verify_args *meta /* host */, const adasd_shard *shard /* host */,
+                              float *tau /* in, out */, const void *cand_all, void *stream);
 
 /*
  * Update step (Section 4.3, Section 4.4 last paragraph; update lines of Algorithm 1).

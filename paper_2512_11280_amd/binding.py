@@ -14,7 +14,8 @@ from typing import Optional
 import torch
 
 F32, BF16 = 0, 1
-ST_BAD_TOKEN, ST_NONFINITE, ST_ZERO_MASS, ST_OVERFLOW, ST_EXACT_PATH, ST_BAD_LENGTH = 1, 2, 4, 8, 16, 32
+ST_BAD_TOKEN, ST_NONFINITE, ST_ZERO_MASS, ST_OVERFLOW, ST_EXACT_PATH, ST_BAD_LENGTH, ST_UNSETTLED = 1, 2, 4, 8, 16, 32, 64
+SHARD_CAND_BYTES = 128
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libadasd.so")
@@ -89,6 +90,11 @@ def load_library():
                                          C.c_void_p]
     L.adasd_verify_shard_decide.argtypes = [C.POINTER(_VerifyArgs), C.POINTER(_Shard), C.c_void_p, C.c_void_p,
                                             C.POINTER(_Options), C.c_void_p]
+    L.adasd_verify_shard_sample.argtypes = [C.POINTER(_VerifyArgs), C.POINTER(_Shard), C.c_void_p, C.c_void_p]
+    L.adasd_verify_shard_pick.argtypes = [C.POINTER(_VerifyArgs), C.POINTER(_Shard), C.c_void_p, C.c_void_p, C.c_void_p]
+    L.adasd_verify_shard_refine.argtypes = [C.POINTER(_VerifyArgs), C.POINTER(_Shard), C.c_void_p, C.c_int, C.c_void_p,
+                                            C.c_void_p]
+    L.adasd_verify_shard_settle.argtypes = [C.POINTER(_VerifyArgs), C.POINTER(_Shard), C.c_void_p, C.c_void_p, C.c_void_p]
     L.adasd_update_thresholds.argtypes = [C.POINTER(_State), C.c_int, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.POINTER(_Options), C.c_void_p,
                                           C.c_void_p]
@@ -369,19 +375,13 @@ def verify_shard_jsd(target_local, draft_local, draft_tokens, workspace: Workspa
     return pos_out
 
 
-def verify_shard_decide(B: int, k: int, dtype, draft_tokens, workspace: Workspace, shard: Shard,
-                        triples_all: torch.Tensor, pos_all: torch.Tensor, state: Optional[State] = None,
-                        draft_len=None, seed: int = 0, seq_id=None, rounds=None, round0: int = 0,
-                        options: Optional[Options] = None, out: Optional[VerifyResult] = None) -> VerifyResult:
-    """adasd_verify_shard_decide: the decisions of the round from the gathered records (no logits)."""
+def _meta_args(B, k, dtype, draft_tokens, workspace, shard, out, state=None, draft_len=None, seed=0, seq_id=None,
+               rounds=None, round0=0):
+    """adasd_verify_args of a replicated call: whole-vocabulary shape, no logits, the outputs."""
     _need(draft_tokens, torch.int32, "draft_tokens")
     _need(draft_len, torch.int32, "draft_len", optional=True)
     _need(seq_id, torch.int32, "seq_id", optional=True)
     _need(rounds, torch.int32, "rounds", optional=True)
-    _need(triples_all, torch.float32, "triples_all")
-    _need(pos_all, torch.float32, "pos_all")
-    if out is None:
-        out = alloc_verify_result(B, k, draft_tokens.device)
     st = state._c() if state is not None else None
     V = shard.V_total
     a = _VerifyArgs(
@@ -391,6 +391,20 @@ def verify_shard_decide(B: int, k: int, dtype, draft_tokens, workspace: Workspac
         out.n_accept.data_ptr(), out.next_token.data_ptr(), out.H_p.data_ptr(), out.H_q.data_ptr(),
         out.d_js.data_ptr(), out.p_accept.data_ptr(), out.accept_mask.data_ptr(),
         out.status.data_ptr(), workspace.ptr, workspace.bytes)
+    a._keep = st            # the struct only holds a pointer to it
+    return a
+
+
+def verify_shard_decide(B: int, k: int, dtype, draft_tokens, workspace: Workspace, shard: Shard,
+                        triples_all: torch.Tensor, pos_all: torch.Tensor, state: Optional[State] = None,
+                        draft_len=None, seed: int = 0, seq_id=None, rounds=None, round0: int = 0,
+                        options: Optional[Options] = None, out: Optional[VerifyResult] = None) -> VerifyResult:
+    """adasd_verify_shard_decide: the decisions of the round from the gathered records (no logits)."""
+    _need(triples_all, torch.float32, "triples_all")
+    _need(pos_all, torch.float32, "pos_all")
+    if out is None:
+        out = alloc_verify_result(B, k, draft_tokens.device)
+    a = _meta_args(B, k, dtype, draft_tokens, workspace, shard, out, state, draft_len, seed, seq_id, rounds, round0)
     opt = options._c() if options is not None else None
     sh = shard._c()
     rc = load_library().adasd_verify_shard_decide(C.byref(a), C.byref(sh), triples_all.data_ptr(),
@@ -398,6 +412,57 @@ def verify_shard_decide(B: int, k: int, dtype, draft_tokens, workspace: Workspac
                                                   C.byref(opt) if opt is not None else None, _stream())
     _check(rc, "adasd_verify_shard_decide")
     return out
+
+
+def verify_shard_sample(target_local, draft_local, draft_tokens, workspace: Workspace, shard: Shard, draft_len=None,
+                        seed: int = 0, seq_id=None, rounds=None, round0: int = 0, top_out=None):
+    """adasd_verify_shard_sample: this holder's best / runner-up record of every sequence."""
+    a = _local_args(target_local, draft_local, draft_tokens, workspace, draft_len, seed, seq_id, rounds, round0)
+    if top_out is None:
+        top_out = torch.empty(a.B, 4, dtype=torch.float32, device=target_local.device)
+    sh = shard._c()
+    _check(load_library().adasd_verify_shard_sample(C.byref(a), C.byref(sh), top_out.data_ptr(), _stream()),
+           "adasd_verify_shard_sample")
+    return top_out
+
+
+def verify_shard_pick(B: int, k: int, dtype, draft_tokens, workspace: Workspace, shard: Shard, top_all: torch.Tensor,
+                      out: VerifyResult, draft_len=None, tau_out=None):
+    """adasd_verify_shard_pick: certain winners into out.next_token; returns tau [B] (+inf where settled)."""
+    _need(top_all, torch.float32, "top_all")
+    if tau_out is None:
+        tau_out = torch.empty(B, dtype=torch.float32, device=draft_tokens.device)
+    a = _meta_args(B, k, dtype, draft_tokens, workspace, shard, out, None, draft_len)
+    sh = shard._c()
+    _check(load_library().adasd_verify_shard_pick(C.byref(a), C.byref(sh), top_all.data_ptr(), tau_out.data_ptr(),
+                                                  _stream()), "adasd_verify_shard_pick")
+    return tau_out
+
+
+def verify_shard_refine(target_local, draft_local, draft_tokens, workspace: Workspace, shard: Shard, tau: torch.Tensor,
+                        draft_len=None, seed: int = 0, seq_id=None, rounds=None, round0: int = 0, cand_out=None,
+                        exact_sums: int = 0):
+    """adasd_verify_shard_refine: this holder's candidates and refined sums of the open sequences."""
+    _need(tau, torch.float32, "tau")
+    a = _local_args(target_local, draft_local, draft_tokens, workspace, draft_len, seed, seq_id, rounds, round0)
+    if cand_out is None:
+        cand_out = torch.empty(a.B, SHARD_CAND_BYTES, dtype=torch.uint8, device=target_local.device)
+    sh = shard._c()
+    _check(load_library().adasd_verify_shard_refine(C.byref(a), C.byref(sh), tau.data_ptr(), exact_sums, cand_out.data_ptr(),
+                                                    _stream()), "adasd_verify_shard_refine")
+    return cand_out
+
+
+def verify_shard_settle(B: int, k: int, dtype, draft_tokens, workspace: Workspace, shard: Shard, tau: torch.Tensor,
+                        cand_all: torch.Tensor, out: VerifyResult, draft_len=None, seed: int = 0, seq_id=None,
+                        rounds=None, round0: int = 0):
+    """adasd_verify_shard_settle: float64 decision of the open sequences into out.next_token / out.status."""
+    _need(tau, torch.float32, "tau")
+    _need(cand_all, torch.uint8, "cand_all")
+    a = _meta_args(B, k, dtype, draft_tokens, workspace, shard, out, None, draft_len, seed, seq_id, rounds, round0)
+    sh = shard._c()
+    _check(load_library().adasd_verify_shard_settle(C.byref(a), C.byref(sh), tau.data_ptr(), cand_all.data_ptr(),
+                                                    _stream()), "adasd_verify_shard_settle")
 
 
 def update_thresholds(state: State, k_max: int, n_accept: torch.Tensor, H_q: torch.Tensor,

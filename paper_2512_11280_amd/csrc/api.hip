@@ -513,6 +513,67 @@ int adasd_verify_shard_decide(const adasd_verify_args* meta, const adasd_shard* 
   return ADASD_OK;
 }
 
+int adasd_verify_shard_sample(const adasd_verify_args* local, const adasd_shard* sh, float* top_out, void* stream) {
+  VerifySetup v;
+  int rc = verify_setup(local, nullptr, kWantLogits, &v);
+  if (rc) return rc < 0 ? rc : ADASD_OK;
+  rc = check_shard(sh, local->V, true);
+  if (rc) return rc;
+  if (!top_out) return ADASD_ERR_INVALID_ARG;
+  if (!aligned_to(top_out, 16)) return ADASD_ERR_MISALIGNED;
+  hipStream_t st = (hipStream_t)stream;
+  Scope sc(3, st);
+  const SampleArgs s = sample_args(local, v);
+  return launch_shard_sample(s, sample_split(local->V, (int)local->dt), sh->col_begin, v.ws,
+                             reinterpret_cast<float4*>(top_out), st) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
+}
+
+int adasd_verify_shard_pick(const adasd_verify_args* meta, const adasd_shard* sh, const float* top_all, float* tau_out,
+                            void* stream) {
+  VerifySetup v;
+  int rc = verify_setup(meta, nullptr, kWantToken, &v);
+  if (rc) return rc < 0 ? rc : ADASD_OK;
+  rc = check_shard(sh, meta->V, false);
+  if (rc) return rc;
+  if (!top_all || !tau_out) return ADASD_ERR_INVALID_ARG;
+  if (!aligned_to(top_all, 16) || !aligned_to(tau_out, 4)) return ADASD_ERR_MISALIGNED;
+  hipStream_t st = (hipStream_t)stream;
+  Scope sc(3, st);
+  return launch_shard_pick(meta->B, sh->n_shards, reinterpret_cast<const float4*>(top_all), v.ws, meta->next_token,
+                           meta->status, tau_out, st) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
+}
+
+int adasd_verify_shard_refine(const adasd_verify_args* local, const adasd_shard* sh, const float* tau, int exact_sums,
+                              void* cand_out, void* stream) {
+  VerifySetup v;
+  int rc = verify_setup(local, nullptr, kWantLogits, &v);
+  if (rc) return rc < 0 ? rc : ADASD_OK;
+  rc = check_shard(sh, local->V, true);
+  if (rc) return rc;
+  if (!tau || !cand_out || (exact_sums != 0 && exact_sums != 1)) return ADASD_ERR_INVALID_ARG;
+  if (!aligned_to(tau, 4) || !aligned_to(cand_out, 16)) return ADASD_ERR_MISALIGNED;
+  hipStream_t st = (hipStream_t)stream;
+  Scope sc(3, st);
+  const SampleArgs s = sample_args(local, v);
+  return launch_shard_refine(s, sample_split(local->V, (int)local->dt), sh->col_begin, tau, exact_sums, v.ws, cand_out, st) == hipSuccess
+             ? ADASD_OK : ADASD_ERR_HIP;
+}
+
+int adasd_verify_shard_settle(const adasd_verify_args* meta, const adasd_shard* sh, float* tau, const void* cand_all,
+                              void* stream) {
+  VerifySetup v;
+  int rc = verify_setup(meta, nullptr, kWantToken, &v);
+  if (rc) return rc < 0 ? rc : ADASD_OK;
+  rc = check_shard(sh, meta->V, false);
+  if (rc) return rc;
+  if (!tau || !cand_all) return ADASD_ERR_INVALID_ARG;
+  if (!aligned_to(tau, 4) || !aligned_to(cand_all, 16)) return ADASD_ERR_MISALIGNED;
+  hipStream_t st = (hipStream_t)stream;
+  Scope sc(3, st);
+  const SampleArgs s = sample_args(meta, v);
+  return launch_shard_settle(s, sh->n_shards, tau, cand_all, v.ws, st) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
+}
+
 int adasd_update_thresholds(const adasd_state* st, int k_max, const int32_t* n_accept,
                             const int32_t* draft_len, const float* H_q, const float* d_js,
                             const adasd_options* opt, uint32_t* status, void* stream) {

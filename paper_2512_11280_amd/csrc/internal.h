@@ -177,6 +177,13 @@ struct SampleArgs {
   int32_t* next_token;
   uint32_t* status;
 };
+hipError_t launch_shard_sample(const SampleArgs& a, int S, int col0, const Workspace& ws, float4* top_out, hipStream_t st);
+hipError_t launch_shard_pick(int B, int G, const float4* top_all, const Workspace& ws, int32_t* next_token,
+                             uint32_t* status, float* tau_out, hipStream_t st);
+hipError_t launch_shard_refine(const SampleArgs& a, int S, int col0, const float* tau, int exact, const Workspace& ws,
+                               void* cand_out, hipStream_t st);
+hipError_t launch_shard_settle(const SampleArgs& a, int G, float* tau, const void* cand_all, const Workspace& ws,
+                               hipStream_t st);
 hipError_t launch_sample(const SampleArgs& a, int S, const Workspace& ws, hipStream_t st);
 
 hipError_t launch_update(const UpdateArgs& a, hipStream_t st);

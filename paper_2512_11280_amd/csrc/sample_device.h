@@ -225,8 +225,9 @@ struct RefineShared {
 // Normaliser of a row to float64 accuracy in the arguments and one float ulp per term: sum of
 // 2^(z log2 e - c) around a first value c of the normaliser, each term the hardware exponential of the
 // float part of the argument times the first-order factor of the remainder.  Returns ln sum exp z.
+// (the sum itself, all threads get it: column shards add theirs up before the logarithm)
 template <int DT>
-__device__ double row_lse_refined(const char* row, int V, double c_lse2, double* sh) {
+__device__ double row_pow2_sum_refined(const char* row, int V, double c_lse2, double* sh) {
   constexpr int EPV = Elem<DT>::per_vec;
   auto term = [&](float z) {
     const double x = (double)z * 1.44269504088896340736 - c_lse2;
@@ -255,19 +256,23 @@ __device__ double row_lse_refined(const char* row, int V, double c_lse2, double*
     }
   }
   for (int v = nv * EPV + tid; v < V; v += kBlock) acc += term(load_elem<DT>(row, v));
-  acc = block_sum_d(acc, sh);
+  return block_sum_d(acc, sh);
+}
+template <int DT>
+__device__ double row_lse_refined(const char* row, int V, double c_lse2, double* sh) {
+  const double acc = row_pow2_sum_refined<DT>(row, V, c_lse2, sh);
   return (c_lse2 + log(acc) * 1.44269504088896340736) * 0.69314718055994530942;
 }
 
-// Settles a sequence among the elements whose upper-bound key is at least tau.  All threads of the
-// workgroup call it; returns the token, or -1 if the decision needs the whole row in float64.
+// Collects into R.cand the elements (vocabulary indices) whose upper-bound key is at least tau, from the
+// per-slice records of the scan (a slice whose runner-up also reaches tau is scanned again).  All threads
+// of the workgroup call it; false: more candidates or slices than the lists hold.  col0: vocabulary index
+// of the row's first element (the rows are column slices of V elements when it is not 0).
 template <int DT>
-__device__ int sample_refine(const char* prow, const char* qrow, int mode, int excluded, int V, int b, int S,
-                             float tau, float cp, float cq, double lse2_p, double lse2_q, uint32_t c1,
-                             uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1, const Workspace& ws,
-                             double* sh_red, RefineShared& R) {
+__device__ bool refine_gather(const char* prow, const char* qrow, bool residual, int excluded, int V, int col0, int b,
+                              int S, float tau, float cp, float cq, uint32_t c1, uint32_t c2, uint32_t c3,
+                              uint32_t k0, uint32_t k1, const Workspace& ws, RefineShared& R) {
   const int tid = threadIdx.x;
-  const bool residual = mode == kResidual;
   if (tid == 0) R.n_cand = R.n_rescan = 0;
   __syncthreads();
   // per-slice records: the slice's best element if it reaches tau; the slice itself if its runner-up does
@@ -285,7 +290,7 @@ __device__ int sample_refine(const char* prow, const char* qrow, int mode, int e
   }
   __syncthreads();
   const int n_rescan = R.n_rescan;
-  if (n_rescan > kMaxRescan) return -1;
+  if (n_rescan > kMaxRescan) return false;
   const bool fast = (reinterpret_cast<uintptr_t>(prow) & 15u) == 0 &&
                     (!residual || (reinterpret_cast<uintptr_t>(qrow) & 15u) == 0);
   for (int n = 0; n < n_rescan; ++n) {
@@ -293,19 +298,33 @@ __device__ int sample_refine(const char* prow, const char* qrow, int mode, int e
     slice_ranges<DT>(fast, V, R.rescan[n], S, lo[0], hi[0], lo[1], hi[1]);
     for (int part = 0; part < 2; ++part)
       for (int v = lo[part] + tid; v < hi[part]; v += kBlock) {
-        const U4 r = philox4x32_10((uint32_t)v >> 2, c1, c2, c3, k0, k1);
+        const int gv = col0 + v;
+        const U4 r = philox4x32_10((uint32_t)gv >> 2, c1, c2, c3, k0, k1);
         const float zp = load_elem<DT>(prow, v);
-        const float k = residual ? key_ub<true>(zp, load_elem<DT>(qrow, v), cp, cq, pick_word(r, v))
-                                 : key_ub<false>(zp, 0.f, cp, cq, pick_word(r, v));
-        if (k >= tau && v != excluded) {
+        const float k = residual ? key_ub<true>(zp, load_elem<DT>(qrow, v), cp, cq, pick_word(r, gv))
+                                 : key_ub<false>(zp, 0.f, cp, cq, pick_word(r, gv));
+        if (k >= tau && gv != excluded) {
           const int at = atomicAdd(&R.n_cand, 1);
-          if (at < kMaxCand) R.cand[at] = v;
+          if (at < kMaxCand) R.cand[at] = gv;
         }
       }
   }
   __syncthreads();
+  return R.n_cand <= kMaxCand;
+}
+
+// Settles a sequence among the elements whose upper-bound key is at least tau.  All threads of the
+// workgroup call it; returns the token, or -1 if the decision needs the whole row in float64.
+template <int DT>
+__device__ int sample_refine(const char* prow, const char* qrow, int mode, int excluded, int V, int b, int S,
+                             float tau, float cp, float cq, double lse2_p, double lse2_q, uint32_t c1,
+                             uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1, const Workspace& ws,
+                             double* sh_red, RefineShared& R) {
+  const int tid = threadIdx.x;
+  const bool residual = mode == kResidual;
+  if (!refine_gather<DT>(prow, qrow, residual, excluded, V, 0, b, S, tau, cp, cq, c1, c2, c3, k0, k1, ws, R)) return -1;
   const int n_cand = R.n_cand;
-  if (n_cand > kMaxCand || n_cand == 0) return -1;
+  if (n_cand == 0) return -1;
   // float64 keys of the candidates.  Without a draft row the normaliser is a common shift and drops
   // out; with it both normalisers are refined first (workgroup-wide), and each key carries the bound
   // 2^-21 (p + q) / w of what their remaining error can do to ln w.

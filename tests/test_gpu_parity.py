@@ -461,6 +461,110 @@ def test_column_sharded_statistics_and_decisions(am, wl, oracle, G_, opt):
             assert np.array_equal(hb[k], host[k]), k
 
 
+def _sharded_tokens(am, batch, ctx, outs, seq_id=None):
+    """Stages 4-7 on one device, after _sharded_decisions: the token of every sequence on every replica."""
+    outs_, states, wss, shards, views, _ = ctx
+    B, K = batch.B, batch.k
+    n_sh = len(shards)
+    x = batch.draft_tokens.cuda()
+    dl = G.to_dev(batch.draft_len)
+    sid = None if seq_id is None else torch.tensor(np.asarray(seq_id, dtype=np.uint32).view(np.int32)).cuda()
+    kw = dict(draft_len=dl, seed=batch.seed, seq_id=sid, round0=batch.round0)
+    top_all = torch.empty(n_sh, B, 4, device="cuda")
+    cand_all = torch.empty(n_sh, B, am.binding.SHARD_CAND_BYTES, dtype=torch.uint8, device="cuda")
+    for g in range(n_sh):
+        am.verify_shard_sample(views[g][0], views[g][1], x, wss[g], shards[g], top_out=top_all[g], **kw)
+    taus = [am.verify_shard_pick(B, K, batch.target.dtype, x, wss[g], shards[g], top_all, outs[g], draft_len=dl)
+            for g in range(n_sh)]
+    open_after_pick = int(torch.isfinite(taus[0]).sum())
+    for exact in (0, 1):               # the second pass (float64-exact sums) only works on what the first left open
+        for g in range(n_sh):
+            am.verify_shard_refine(views[g][0], views[g][1], x, wss[g], shards[g], taus[g], cand_out=cand_all[g],
+                                   exact_sums=exact, **kw)
+        for g in range(n_sh):
+            am.verify_shard_settle(B, K, batch.target.dtype, x, wss[g], shards[g], taus[g], cand_all, outs[g], **kw)
+        torch.cuda.synchronize()
+        if exact == 0:
+            open_after_first = int(torch.isfinite(taus[0]).sum())
+    return open_after_pick, open_after_first
+
+
+@pytest.mark.parametrize("n_sh", [1, 3, 8])
+@pytest.mark.parametrize("opt", [dict(), dict(base_test=1, list_update=1)], ids=["default", "literal"])
+def test_column_sharded_round_gives_the_oracles_tokens(am, wl, oracle, n_sh, opt):
+    batch = wl.config_batched(B=8, k=6, V=32000, seed=500 + n_sh, cap=96)
+    batch.draft_len = torch.tensor([6, 0, 3, 6, 5, 6, 1, 6], dtype=torch.int32)
+    batch.target[5, 6, 17] = float("inf")                      # broken bonus row (only matters if it is sampled)
+    options = am.Options(**opt)
+    ctx = _sharded_decisions(am, batch, n_sh, options=options)
+    outs = ctx[0]
+    _sharded_tokens(am, batch, ctx, outs)
+    ref = G.run_oracle(oracle, batch, options=options)
+    for o in outs[1:]:
+        assert torch.equal(o.next_token, outs[0].next_token) and torch.equal(o.status, outs[0].status)
+    rep = G.compare_verify(outs[0], ref)
+    _report(f"sharded round G={n_sh} {opt}", rep)
+    assert rep["flips"] == 0
+    assert (outs[0].status & am.binding.ST_UNSETTLED == 0).all()
+    # the whole-vocabulary call gives the same integers
+    whole, _, _ = G.run_gpu(am, batch, options=options)
+    assert torch.equal(whole.next_token, outs[0].next_token) and torch.equal(whole.n_accept, outs[0].n_accept)
+
+
+@pytest.mark.parametrize("mode", ["residual", "bonus", "exclude"])
+@pytest.mark.parametrize("dtype,V", [(torch.bfloat16, 4104), (torch.float32, 2056)], ids=["bf16", "f32"])
+def test_column_sharded_near_ties_are_settled_from_the_exchanged_candidates(am, wl, oracle, mode, dtype, V):
+    g = torch.Generator().manual_seed(V)
+    t = (torch.randn(1, 2, V, generator=g) * 2.5).to(dtype)
+    d = (t[:, :1].float() + torch.randn(1, 1, V, generator=g)).to(dtype)
+    p = torch.softmax(t[0, 0].double(), -1)
+    q = torch.softmax(d[0, 0].double(), -1)
+    n = 100000
+    x = int(torch.argmax(q - p)) if mode == "residual" else int(torch.argmax(p - q))
+    opt = dict(relaxed_off=1)
+    if mode == "exclude":
+        opt["base_test"] = 1
+        x = int(torch.argmin(p))
+    ref = oracle.verify(t, d, np.full((n, 1), x, np.int32), seed=41, shared_rows=True, **opt)
+    sel = (ref["n_accept"] == (1 if mode == "bonus" else 0))
+    close_call = np.flatnonzero(sel & (ref["top2_gap"] < 1e-4))[:16]
+    assert len(close_call) >= 2
+    ids = close_call.astype(np.uint32)
+    B = len(ids)
+    batch = wl.VerifyBatch(t.repeat(B, 1, 1).contiguous(), d.repeat(B, 1, 1).contiguous(),
+                           torch.full((B, 1), x, dtype=torch.int32), None, wl.empty_state(B, 8), 41)
+    options = am.Options(**opt)
+    ctx = _sharded_decisions(am, batch, 4, options=options, seq_id=ids)
+    outs = ctx[0]
+    n_open, n_open2 = _sharded_tokens(am, batch, ctx, outs, seq_id=ids)
+    refb = G.run_oracle(oracle, batch, options=options, seq_id=ids)
+    assert np.array_equal(refb["next_token"], ref["next_token"][close_call])
+    rep = G.compare_verify(outs[0], refb)
+    st = outs[0].status.cpu().numpy()
+    print(f"[sharded near ties] {mode} V={V}: {B} draws, {n_open} open after the pick, {n_open2} after the first "
+          f"settle, {(st & 16 != 0).sum()} settled in float64", flush=True)
+    assert rep["flips"] == 0 and (st & am.binding.ST_UNSETTLED == 0).all() and (st & 16 != 0).sum() >= 1
+
+
+def test_column_sharded_draw_without_certain_mass_is_flagged(am, wl, oracle):
+    """Identical target and draft rows with a broken draft token: the rejection leaves a residual without
+    mass, which only the whole-row float64 path of the unsharded call can turn into a draw."""
+    V = 2048
+    g = torch.Generator().manual_seed(4)
+    z = (torch.randn(V, generator=g) * 2).to(torch.bfloat16)
+    t = z.repeat(2, 2, 1).clone()
+    d = z.repeat(2, 1, 1).clone()
+    tok = torch.tensor([[V + 5], [3]], dtype=torch.int32)
+    batch = wl.VerifyBatch(t, d, tok, None, wl.empty_state(2, 8), 11)
+    ctx = _sharded_decisions(am, batch, 2)
+    outs = ctx[0]
+    _sharded_tokens(am, batch, ctx, outs)
+    st = outs[0].status.cpu().numpy()
+    assert st[0] & am.binding.ST_UNSETTLED and st[0] & am.binding.ST_BAD_TOKEN
+    ref = G.run_oracle(oracle, batch)
+    assert st[1] == 0 and outs[0].next_token[1].item() == ref["next_token"][1]       # accepted: bonus token as usual
+
+
 def test_column_sharded_argument_errors(am):
     ws = am.Workspace(2, 2, 64, torch.float32)
     t = torch.zeros(2, 3, 64, device="cuda")
