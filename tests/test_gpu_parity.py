@@ -780,6 +780,18 @@ def test_draft_step_draws_the_oracles_tokens(am, wl, oracle, dtype, V):
     assert G.close(H, Href).all()
 
 
+@pytest.mark.parametrize("B,V", [(2000, 20011), (3000, 4099)], ids=["fewer-slices", "dense-counters"])
+def test_draft_step_many_rows(am, wl, oracle, B, V):
+    """Many rows: the slices per row are halved until the grid fits, and the arrival counters of the rows
+    no longer get a cache line each."""
+    g = torch.Generator().manual_seed(B)
+    z = (torch.randn(B, V, generator=g) * 2).to(torch.bfloat16)
+    H, stop, tok, st, ref_tok, gap = _draft_step_case(am, oracle, z, step=1, k_max=9, seed=5, round0=2)
+    assert np.array_equal(tok, ref_tok), np.flatnonzero(tok != ref_tok)
+    Href, _ = oracle.draft_entropy(z, step=1, k_max=9)
+    assert G.close(H, Href).all()
+
+
 def test_draft_step_unaligned_rows_and_broken_rows(am, wl, oracle):
     g = torch.Generator().manual_seed(3)
     B, V = 6, 4099                                       # odd row length: most rows are not 16-byte aligned
