@@ -378,6 +378,19 @@ def test_long_history_with_the_update_in_the_same_call_and_status_bits(am, wl, o
         assert np.array_equal(hb[k], host[k]), k
 
 
+def test_many_sequences_with_long_histories(am, wl, oracle):
+    """More sequences than the arrival-counter arrays have cache lines: the counters of neighbouring
+    sequences share lines again, in the sampling kernel and in the per-position decision kernel."""
+    B, cap = 1200, 600
+    batch = wl.config_batched(B=B, k=2, V=520, seed=12, cap=cap)
+    g = torch.Generator().manual_seed(3)
+    batch.state = wl.threshold_state(B, cap, g, n_hist=500)
+    out, _, _ = G.run_gpu(am, batch, options=am.Options(apply_update=1))
+    ref = G.run_oracle(oracle, batch)
+    rep = G.compare_verify(out, ref, info_bits=16 | 8)
+    _report("many sequences", rep)
+
+
 def test_long_history_largest_window(am, wl, oracle):
     cap = 2000
     batch = wl.config_batched(B=2, k=64, V=4099, seed=6, cap=cap)
