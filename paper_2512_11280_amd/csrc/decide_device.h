@@ -440,63 +440,89 @@ __device__ inline void update_sequence(const UpdateArgs& a, int b, int lane, int
 // sequence's decisions (first rejection, sampling plan, status, update step).
 // ---------------------------------------------------------------------------------------------
 struct WideShared {
-  double m[kWaves], s[kWaves];
+  double m[2][kWaves], s[2][kWaves];
   int last;
   int n_pass;           // in-loop appends: earlier positions of this round that pass the filter
 };
 
-// ln [ p(d | list) P(list) ] by the whole workgroup; the list continues in X (nx samples).
+constexpr int kWideU = 16;   // samples per thread in flight: one workgroup walks a list alone, so the latency of
+                             // a load is only hidden by the thread's own other loads
+
+// One batch of kernel exponents joins a thread's running maximum m and rescaled sum s: the batch's
+// largest exponent first, then ONE rescale of the old sum.  valid: how many of x[] hold samples.
+__device__ __forceinline__ void joint_terms(double d, const float (&x)[kWideU], int first, int nt, double inv2h2,
+                                            double& m, double& s) {
+  double t[kWideU];
+  double hi = m;
+#pragma unroll
+  for (int u = 0; u < kWideU; ++u) {
+    const double e = d - (double)x[u];
+    t[u] = first + u * kBlock < nt ? -(e * e) * inv2h2 : -INFINITY;
+    hi = fmax(hi, t[u]);
+  }
+  if (hi > -INFINITY) {                  // (a thread past the end of the list has nothing to add)
+    // all exponents are <= 0; with m = -inf the old sum is 0 and its factor 2^-inf = 0
+    float add = 0.f;
+#pragma unroll
+    for (int u = 0; u < kWideU; ++u) add += ex2((float)((t[u] - hi) * 1.44269504088896340736));
+    s = s * (double)ex2((float)((m - hi) * 1.44269504088896340736)) + (double)add;
+    m = hi;
+  }
+}
+
+// Workgroup-wide log-sum of N lists' per-thread (m, s) pairs at once: common maximum, rescaled sums (a
+// thread without samples has s = 0).  out[q] = ln sum_j exp(t_j) of list q.
+template <int N>
+__device__ __forceinline__ void joint_reduce(const double (&m)[N], const double (&s)[N], WideShared& w, double (&out)[N]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  double M[N], sc[N];
+#pragma unroll
+  for (int q = 0; q < N; ++q) {
+    M[q] = half_max_d(m[q]);
+    M[q] = fmax(M[q], __shfl_xor(M[q], 32));
+    sc[q] = m[q] > -INFINITY ? s[q] * (double)ex2((float)((m[q] - M[q]) * 1.44269504088896340736)) : 0.0;
+    sc[q] = half_sum_d(sc[q]);
+    sc[q] += __shfl_xor(sc[q], 32);
+  }
+  __syncthreads();
+  if (lane == 0) {
+#pragma unroll
+    for (int q = 0; q < N; ++q) {
+      w.m[q][wave] = M[q];
+      w.s[q][wave] = sc[q];
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < N; ++q) {
+    double Mb = w.m[q][0];
+#pragma unroll
+    for (int v = 1; v < kWaves; ++v) Mb = fmax(Mb, w.m[q][v]);
+    double total = 0.0;
+#pragma unroll
+    for (int v = 0; v < kWaves; ++v)
+      total += w.m[q][v] > -INFINITY ? w.s[q][v] * (double)ex2((float)((w.m[q][v] - Mb) * 1.44269504088896340736)) : 0.0;
+    out[q] = Mb + kLn2 * log2_acc((float)total);
+  }
+}
+
+// ln [ p(d | list) P(list) ] by the whole workgroup, streaming a list of any length; the list continues
+// in X (nx samples).
 __device__ inline double block_log_joint(double d, const float* L, int n, const float* X, int nx, const Kde& k,
                                          WideShared& w) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nt = n + nx;
-  double m = -INFINITY, s = 0.0;
-  constexpr int U = 16;                    // samples per thread in flight: one workgroup walks the list alone, so the
-                                           // latency of a load is only hidden by the thread's own other loads
-  for (int base = 0; base < nt; base += U * kBlock) {
-    float x[U];
+  const int tid = threadIdx.x, nt = n + nx;
+  double m[1] = {-INFINITY}, s[1] = {0.0}, out[1];
+  for (int base = 0; base < nt; base += kWideU * kBlock) {
+    float x[kWideU];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
+    for (int u = 0; u < kWideU; ++u) {
       const int j = min(base + tid + u * kBlock, nt - 1);
       x[u] = j < n ? L[j] : X[j - n];
     }
-    // exponents of the batch, its maximum joins the running one, then ONE rescale of the old sum
-    double t[U];
-    double hi = m;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const double e = d - (double)x[u];
-      t[u] = base + tid + u * kBlock < nt ? -(e * e) * k.inv2h2 : -INFINITY;
-      hi = fmax(hi, t[u]);
-    }
-    if (hi > -INFINITY) {                  // (a thread past the end of the list has nothing to add)
-      // all exponents are <= 0; with m = -inf the old sum is 0 and its factor 2^-inf = 0
-      float add = 0.f;
-#pragma unroll
-      for (int u = 0; u < U; ++u) add += ex2((float)((t[u] - hi) * 1.44269504088896340736));
-      s = s * (double)ex2((float)((m - hi) * 1.44269504088896340736)) + (double)add;
-      m = hi;
-    }
+    joint_terms(d, x, base + tid, nt, k.inv2h2, m[0], s[0]);
   }
-  // wavefront, then workgroup: common maximum, rescaled sums (a thread without samples has s = 0)
-  double M = half_max_d(m);
-  M = fmax(M, __shfl_xor(M, 32));
-  double sc = m > -INFINITY ? s * (double)ex2((float)((m - M) * 1.44269504088896340736)) : 0.0;
-  sc = half_sum_d(sc);
-  sc += __shfl_xor(sc, 32);
-  __syncthreads();
-  if (lane == 0) {
-    w.m[wave] = M;
-    w.s[wave] = sc;
-  }
-  __syncthreads();
-  double Mb = w.m[0];
-#pragma unroll
-  for (int q = 1; q < kWaves; ++q) Mb = fmax(Mb, w.m[q]);
-  double total = 0.0;
-#pragma unroll
-  for (int q = 0; q < kWaves; ++q)
-    total += w.m[q] > -INFINITY ? w.s[q] * (double)ex2((float)((w.m[q] - Mb) * 1.44269504088896340736)) : 0.0;
-  return Mb + kLn2 * log2_acc((float)total) - k.log_norm;
+  joint_reduce<1>(m, s, w, out);
+  return out[0] - k.log_norm;
 }
 
 template <int DT, bool INLOOP>
@@ -572,30 +598,52 @@ __device__ void decide_position_wide(const DecideArgs& a, const UpdateArgs& upd,
     if (!a.relaxed_off && !bad && LA && n_i >= min_n && nR >= min_n) {      // uniform over the workgroup
       const double cA = nA > 0 ? (double)LA[0] : (double)sh.extra[0], cR = (double)LR[0];
       double m[4] = {0.0, 0.0, 0.0, 0.0};
-      constexpr int U = 16;                // loads in flight per thread, as in block_log_joint
-      for (int base = 0; base < n_i; base += U * kBlock) {
-        float x[U];
+      constexpr int U = kWideU;
+      // Lists of up to U samples per thread are read ONCE, both at the same time, and stay in registers for
+      // the moments and for the kernel sums; longer ones are streamed twice.
+      const bool resident = n_i <= U * kBlock && nR <= U * kBlock;
+      float xa[U], xr[U];
+      if (resident) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          const int j = min(base + tid + u * kBlock, n_i - 1);
-          x[u] = j < nA ? LA[j] : sh.extra[j - nA];
+          const int ja = min(tid + u * kBlock, n_i - 1), jr = min(tid + u * kBlock, nR - 1);
+          xa[u] = ja < nA ? LA[ja] : sh.extra[ja - nA];
+          xr[u] = LR[jr];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          const double e = base + tid + u * kBlock < n_i ? (double)x[u] - cA : 0.0;
-          m[0] += e;
-          m[1] += e * e;
+          const double ea = tid + u * kBlock < n_i ? (double)xa[u] - cA : 0.0;
+          const double er = tid + u * kBlock < nR ? (double)xr[u] - cR : 0.0;
+          m[0] += ea;
+          m[1] += ea * ea;
+          m[2] += er;
+          m[3] += er * er;
         }
-      }
-      for (int base = 0; base < nR; base += U * kBlock) {
-        float x[U];
+      } else {
+        for (int base = 0; base < n_i; base += U * kBlock) {
+          float x[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) x[u] = LR[min(base + tid + u * kBlock, nR - 1)];
+          for (int u = 0; u < U; ++u) {
+            const int j = min(base + tid + u * kBlock, n_i - 1);
+            x[u] = j < nA ? LA[j] : sh.extra[j - nA];
+          }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const double e = base + tid + u * kBlock < nR ? (double)x[u] - cR : 0.0;
-          m[2] += e;
-          m[3] += e * e;
+          for (int u = 0; u < U; ++u) {
+            const double e = base + tid + u * kBlock < n_i ? (double)x[u] - cA : 0.0;
+            m[0] += e;
+            m[1] += e * e;
+          }
+        }
+        for (int base = 0; base < nR; base += U * kBlock) {
+          float x[U];
+#pragma unroll
+          for (int u = 0; u < U; ++u) x[u] = LR[min(base + tid + u * kBlock, nR - 1)];
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const double e = base + tid + u * kBlock < nR ? (double)x[u] - cR : 0.0;
+            m[2] += e;
+            m[3] += e * e;
+          }
         }
       }
 #pragma unroll
@@ -612,8 +660,18 @@ __device__ void decide_position_wide(const DecideArgs& a, const UpdateArgs& upd,
       for (int x = 0; x < 4; ++x) m[x] = (sh.mom[0][x] + sh.mom[1][x]) + (sh.mom[2][x] + sh.mom[3][x]);
       Kde kA, kR;
       if (kde_constants(m[0], m[1], n_i, nR, a.bw_rule, &kA) && kde_constants(m[2], m[3], nR, n_i, a.bw_rule, &kR)) {
-        const double ja = block_log_joint(d, LA, nA, sh.extra, ne, kA, wsh);
-        const double jr = block_log_joint(d, LR, nR, nullptr, 0, kR, wsh);
+        double ja, jr;
+        if (resident) {
+          double mm[2] = {-INFINITY, -INFINITY}, ss[2] = {0.0, 0.0}, out[2];
+          joint_terms(d, xa, tid, n_i, kA.inv2h2, mm[0], ss[0]);
+          joint_terms(d, xr, tid, nR, kR.inv2h2, mm[1], ss[1]);
+          joint_reduce<2>(mm, ss, wsh, out);
+          ja = out[0] - kA.log_norm;
+          jr = out[1] - kR.log_norm;
+        } else {
+          ja = block_log_joint(d, LA, nA, sh.extra, ne, kA, wsh);
+          jr = block_log_joint(d, LR, nR, nullptr, 0, kR, wsh);
+        }
         PA = 1.0 / (1.0 + (double)ex2((float)((jr - ja) * 1.44269504088896340736)));
       }
     }
