@@ -48,6 +48,8 @@ def main():
                     help="also time one holder's calls of the column-sharded path with this many holders "
                          "(its V/G columns of the same workload; the other holders' records are computed "
                          "beforehand), reported under 'sharded'")
+    ap.add_argument("--no-running-sums", action="store_true",
+                    help="state without adasd_state.mom: the decision stage adds the history lists up in every call")
     ap.add_argument("--literal", action="store_true",
                     help="time the variant that follows Algorithm 1's loop as written (options base_test=1, "
                          "list_update=1) instead of the default readings")
@@ -77,7 +79,7 @@ def main():
             host0 = batch
         sets.append((batch.target.cuda(), batch.draft.cuda(), batch.draft_tokens.cuda(), batch.seed))
     ws = am.Workspace(B, K, V, torch.bfloat16)
-    state = am.State(B, LIST_CAP).load(host0.state)
+    state = am.State(B, LIST_CAP, running_sums=not args.no_running_sums).load(host0.state)
     out = am.binding.alloc_verify_result(B, K)
     torch.cuda.synchronize()
 

@@ -88,6 +88,13 @@ typedef struct {
   float *LR;        /* [B,cap]  JS distances of rejected candidates, values in (0,1) (L_D^R) */
   int32_t *nA;      /* [B]      |L_D^A| */
   int32_t *nR;      /* [B]      |L_D^R| */
+  double *mom;      /* [B,4] or NULL.  Running sums of long lists for the bandwidth of the Bayesian test
+                       (Section 4.4): sum and sum of squares of (x - LA[b,0]) over L_D^A, then of
+                       (x - LR[b,0]) over L_D^R.  A pair is valid, kept by the update step and used by the
+                       decision stage once its list holds 4096 samples (shorter lists are added up in
+                       every call: they fit the registers of one workgroup); after writing the lists by
+                       other means call adasd_state_refresh.  NULL: lists of any length are added up in
+                       every call (one more pass over them). */
 } adasd_state;
 
 /*
@@ -145,6 +152,8 @@ int adasd_workspace_init(void *workspace, size_t ws_bytes, void *stream);
 
 /* Algorithm 1, initialisation: empty lists, T_G = 0.  `st` is a host struct of device pointers. */
 int adasd_state_init(const adasd_state *st, void *stream);
+/* Recomputes st->mom from the lists as they are (no-op when st->mom is NULL). */
+int adasd_state_refresh(const adasd_state *st, void *stream);
 
 /*
  * Draft side (Section 4.3; generation loop of Algorithm 1).  For every active row b:

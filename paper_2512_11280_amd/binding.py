@@ -32,7 +32,7 @@ class AdasdError(RuntimeError):
 class _State(C.Structure):
     _fields_ = [("B", C.c_int32), ("cap", C.c_int32), ("T_G", C.c_void_p), ("ent_sum", C.c_void_p),
                 ("ent_cnt", C.c_void_p), ("LA", C.c_void_p), ("LR", C.c_void_p),
-                ("nA", C.c_void_p), ("nR", C.c_void_p)]
+                ("nA", C.c_void_p), ("nR", C.c_void_p), ("mom", C.c_void_p)]
 
 
 class _Options(C.Structure):
@@ -77,6 +77,7 @@ def load_library():
     L.adasd_workspace_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
     L.adasd_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
     L.adasd_state_init.argtypes = [C.POINTER(_State), C.c_void_p]
+    L.adasd_state_refresh.argtypes = [C.POINTER(_State), C.c_void_p]
     L.adasd_draft_step.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_void_p, C.c_void_p,
                                    C.c_int, C.c_int, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint32,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
@@ -173,8 +174,11 @@ class Workspace:
 class State:
     """Per-sequence adaptive state (history lists, rejected-entropy sum, generation threshold)."""
 
-    def __init__(self, B: int, cap: int, device="cuda"):
+    def __init__(self, B: int, cap: int, device="cuda", running_sums: bool = True):
+        """running_sums: keep adasd_state.mom (sums of the lists for the bandwidths); without it the
+        decision stage adds the lists up in every call."""
         self.B, self.cap = B, cap
+        self.mom = torch.empty(B, 4, dtype=torch.float64, device=device) if running_sums else None
         self.T_G = torch.empty(B, dtype=torch.float32, device=device)
         self.ent_sum = torch.empty(B, dtype=torch.float64, device=device)
         self.ent_cnt = torch.empty(B, dtype=torch.int32, device=device)
@@ -186,12 +190,13 @@ class State:
 
     def _c(self) -> _State:
         return _State(self.B, self.cap, _p(self.T_G), _p(self.ent_sum), _p(self.ent_cnt),
-                      _p(self.LA), _p(self.LR), _p(self.nA), _p(self.nR))
+                      _p(self.LA), _p(self.LR), _p(self.nA), _p(self.nR), _p(self.mom))
 
     def load(self, host: dict):
         """Copy a host-side state (numpy arrays keyed like the fields) onto the device."""
         for k in ("T_G", "ent_sum", "ent_cnt", "LA", "LR", "nA", "nR"):
             getattr(self, k).copy_(torch.from_numpy(host[k]))
+        _check(load_library().adasd_state_refresh(C.byref(self._c()), _stream()), "adasd_state_refresh")
         return self
 
     def to_host(self) -> dict:

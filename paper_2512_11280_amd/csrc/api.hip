@@ -154,7 +154,7 @@ static int check_state(const adasd_state* st) {
   if (st->cap > 0 && (!st->LA || !st->LR)) return ADASD_ERR_INVALID_ARG;
   if (!aligned_to(st->T_G, 4) || !aligned_to(st->ent_sum, 8) || !aligned_to(st->ent_cnt, 4) ||
       !aligned_to(st->LA, 4) || !aligned_to(st->LR, 4) || !aligned_to(st->nA, 4) ||
-      !aligned_to(st->nR, 4))
+      !aligned_to(st->nR, 4) || !aligned_to(st->mom, 8))
     return ADASD_ERR_MISALIGNED;
   return ADASD_OK;
 }
@@ -170,6 +170,7 @@ static UpdateArgs state_args(const adasd_state* st) {
   u.LR = st->LR;
   u.nA = st->nA;
   u.nR = st->nR;
+  u.mom = st->mom;
   return u;
 }
 
@@ -178,6 +179,14 @@ int adasd_state_init(const adasd_state* st, void* stream) {
   if (rc) return rc;
   UpdateArgs u = state_args(st);
   return launch_state_init(u, (hipStream_t)stream) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
+}
+
+int adasd_state_refresh(const adasd_state* st, void* stream) {
+  int rc = check_state(st);
+  if (rc) return rc;
+  if (!st->mom || st->B == 0) return ADASD_OK;
+  UpdateArgs u = state_args(st);
+  return launch_state_refresh(u, (hipStream_t)stream) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
 }
 
 int adasd_draft_entropy(const void* draft_logits, adasd_dtype dt, int B, int V, int64_t row_stride,
@@ -325,6 +334,7 @@ int verify_setup(const adasd_verify_args* a, const adasd_options* opt_in, int wa
     d.LR = a->state->LR;
     d.nA = a->state->nA;
     d.nR = a->state->nR;
+    d.mom = a->state->mom;
   }
   d.seed_lo = (uint32_t)a->seed;
   d.seed_hi = (uint32_t)(a->seed >> 32);

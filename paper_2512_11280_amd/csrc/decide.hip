@@ -57,6 +57,38 @@ __global__ void __launch_bounds__(64) k_state_init(UpdateArgs a) {
   a.ent_cnt[b] = 0;
   a.nA[b] = 0;
   a.nR[b] = 0;
+  if (a.mom)
+    for (int x = 0; x < 4; ++x) a.mom[4 * b + x] = 0.0;
+}
+
+// Running sums of both lists of one sequence from scratch (one workgroup per sequence).
+__global__ void __launch_bounds__(kBlock) k_state_refresh(UpdateArgs a) {
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nA = min(max(a.nA[b], 0), a.cap), nR = min(max(a.nR[b], 0), a.cap);
+  const float* LA = a.LA + (size_t)b * a.cap;
+  const float* LR = a.LR + (size_t)b * a.cap;
+  const double cA = nA > 0 ? (double)LA[0] : 0.0, cR = nR > 0 ? (double)LR[0] : 0.0;
+  double m[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int j = tid; j < nA; j += kBlock) {
+    const double e = (double)LA[j] - cA;
+    m[0] += e;
+    m[1] += e * e;
+  }
+  for (int j = tid; j < nR; j += kBlock) {
+    const double e = (double)LR[j] - cR;
+    m[2] += e;
+    m[3] += e * e;
+  }
+  __shared__ double sh[kWaves][4];
+#pragma unroll
+  for (int x = 0; x < 4; ++x) {
+    m[x] = half_sum_d(m[x]);
+    m[x] += __shfl_xor(m[x], 32);
+  }
+  if (lane == 0)
+    for (int x = 0; x < 4; ++x) sh[wave][x] = m[x];
+  __syncthreads();
+  if (tid < 4) a.mom[4 * b + tid] = (sh[0][tid] + sh[1][tid]) + (sh[2][tid] + sh[3][tid]);
 }
 
 __global__ void __launch_bounds__(256) k_zero(uint32_t* p, size_t n) {
@@ -101,6 +133,12 @@ hipError_t launch_update(const UpdateArgs& a, hipStream_t st) {
 hipError_t launch_state_init(const UpdateArgs& a, hipStream_t st) {
   if (a.B <= 0) return hipSuccess;
   launch_kernel(k_state_init, dim3((a.B + 63) / 64), dim3(64), st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_state_refresh(const UpdateArgs& a, hipStream_t st) {
+  if (a.B <= 0 || !a.mom) return hipSuccess;
+  launch_kernel(k_state_refresh, dim3(a.B), dim3(kBlock), st, a);
   return hipGetLastError();
 }
 

@@ -227,6 +227,7 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
   if (kde_on) {          // uniform over the workgroup
     cA = nA > 0 ? (double)LA[0] : (double)sh.extra[0];   // (with an empty list the shift is only used once an extra exists)
     cR = (double)LR[0];
+    // (lists this short never have running sums in the state: they are added up here)
     for (int j = tid; j < nA; j += kBlock) {
       const double e = (double)LA[j] - cA;
       m[0] += e;
@@ -404,7 +405,67 @@ __device__ inline void update_sequence_core(const UpdateArgs& a, int b, int lane
   const int nA_new = min(nA + __popcll(acc), a.cap);
   if (nA + __popcll(acc) > a.cap) st |= ADASD_ST_OVERFLOW;
   // the lane of the rejected position finishes the sequence (with all 64 positions accepted: the last lane)
-  if (lane != (r < 64 ? r : 63)) return;
+  const int fin = r < 64 ? r : 63;
+  // Running sums of the lists about their first elements: kept from the moment a list reaches kSumsMin
+  // samples (added up from scratch in that call), so short lists cost nothing here.
+  if (a.mom && (nA_new >= kSumsMin || nR + 1 >= kSumsMin)) {       // (uniform)
+    const bool rej_appended = r < kb && __shfl((int)pass, fin) && nR < a.cap;
+    const int nR_after = nR + (rej_appended ? 1 : 0);
+    const float d_rej = __shfl(d, fin);
+    if (nA_new >= kSumsMin && nA_new > nA) {
+      const float* LAb = a.LA + (size_t)b * a.cap;
+      const double c = (double)LAb[0];          // nA >= kSumsMin - 64 > 0: the first element is an old one
+      double s1 = 0.0, s2 = 0.0;
+      if (nA < kSumsMin) {                       // the list crosses the mark: everything it held before
+        for (int j = lane; j < nA; j += 64) {
+          const double e = (double)LAb[j] - c;
+          s1 += e;
+          s2 += e * e;
+        }
+      }
+      if (pass && lane < r && nA + __popcll(acc & ((1ull << lane) - 1ull)) < a.cap) {
+        const double e = (double)d - c;
+        s1 += e;
+        s2 += e * e;
+      }
+      s1 = half_sum_d(s1);
+      s1 += __shfl_xor(s1, 32);
+      s2 = half_sum_d(s2);
+      s2 += __shfl_xor(s2, 32);
+      if (lane == 0) {
+        const bool fresh = nA < kSumsMin;
+        a.mom[4 * b + 0] = (fresh ? 0.0 : a.mom[4 * b + 0]) + s1;
+        a.mom[4 * b + 1] = (fresh ? 0.0 : a.mom[4 * b + 1]) + s2;
+      }
+    }
+    if (nR_after >= kSumsMin && rej_appended) {
+      const float* LRb = a.LR + (size_t)b * a.cap;
+      const double c = (double)LRb[0];
+      double s1 = 0.0, s2 = 0.0;
+      if (nR < kSumsMin) {
+        for (int j = lane; j < nR; j += 64) {
+          const double e = (double)LRb[j] - c;
+          s1 += e;
+          s2 += e * e;
+        }
+      }
+      if (lane == 0) {
+        const double e = (double)d_rej - c;
+        s1 += e;
+        s2 += e * e;
+      }
+      s1 = half_sum_d(s1);
+      s1 += __shfl_xor(s1, 32);
+      s2 = half_sum_d(s2);
+      s2 += __shfl_xor(s2, 32);
+      if (lane == 0) {
+        const bool fresh = nR < kSumsMin;
+        a.mom[4 * b + 2] = (fresh ? 0.0 : a.mom[4 * b + 2]) + s1;
+        a.mom[4 * b + 3] = (fresh ? 0.0 : a.mom[4 * b + 3]) + s2;
+      }
+    }
+  }
+  if (lane != fin) return;
   int nR_new = nR;
   if (r < kb) {
     if (isfinite(H)) {
@@ -564,6 +625,11 @@ __device__ void decide_position_wide(const DecideArgs& a, const UpdateArgs& upd,
       LA = a.LA + (size_t)b * a.cap;
       LR = a.LR + (size_t)b * a.cap;
     }
+    // the state's running sums of a list are valid once it holds kSumsMin samples; requested with the lengths
+    const bool sums_A = a.mom && LA && nA >= kSumsMin, sums_R = a.mom && LA && nR >= kSumsMin;
+    double mom_pre[4] = {0.0, 0.0, 0.0, 0.0};
+    if (sums_A) { mom_pre[0] = a.mom[4 * b + 0]; mom_pre[1] = a.mom[4 * b + 1]; }
+    if (sums_R) { mom_pre[2] = a.mom[4 * b + 2]; mom_pre[3] = a.mom[4 * b + 3]; }
     int ne = 0;                            // in-loop appends this position sees
     if (INLOOP) {
       // distances of the earlier positions (each workgroup of the sequence forms them for itself)
@@ -620,44 +686,62 @@ __device__ void decide_position_wide(const DecideArgs& a, const UpdateArgs& upd,
           m[3] += er * er;
         }
       } else {
-        for (int base = 0; base < n_i; base += U * kBlock) {
-          float x[U];
+        if (!sums_A)
+          for (int base = 0; base < n_i; base += U * kBlock) {
+            float x[U];
 #pragma unroll
-          for (int u = 0; u < U; ++u) {
-            const int j = min(base + tid + u * kBlock, n_i - 1);
-            x[u] = j < nA ? LA[j] : sh.extra[j - nA];
-          }
+            for (int u = 0; u < U; ++u) {
+              const int j = min(base + tid + u * kBlock, n_i - 1);
+              x[u] = j < nA ? LA[j] : sh.extra[j - nA];
+            }
 #pragma unroll
-          for (int u = 0; u < U; ++u) {
-            const double e = base + tid + u * kBlock < n_i ? (double)x[u] - cA : 0.0;
-            m[0] += e;
-            m[1] += e * e;
+            for (int u = 0; u < U; ++u) {
+              const double e = base + tid + u * kBlock < n_i ? (double)x[u] - cA : 0.0;
+              m[0] += e;
+              m[1] += e * e;
+            }
           }
+        if (!sums_R)
+          for (int base = 0; base < nR; base += U * kBlock) {
+            float x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) x[u] = LR[min(base + tid + u * kBlock, nR - 1)];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+              const double e = base + tid + u * kBlock < nR ? (double)x[u] - cR : 0.0;
+              m[2] += e;
+              m[3] += e * e;
+            }
+          }
+      }
+      const bool both_sums = !resident && sums_A && sums_R;
+      if (!both_sums) {              // (uniform) something was added up by the threads
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          m[x] = half_sum_d(m[x]);
+          m[x] += __shfl_xor(m[x], 32);
         }
-        for (int base = 0; base < nR; base += U * kBlock) {
-          float x[U];
+        if (lane == 0) {
 #pragma unroll
-          for (int u = 0; u < U; ++u) x[u] = LR[min(base + tid + u * kBlock, nR - 1)];
+          for (int x = 0; x < 4; ++x) sh.mom[wave][x] = m[x];
+        }
+        __syncthreads();
 #pragma unroll
-          for (int u = 0; u < U; ++u) {
-            const double e = base + tid + u * kBlock < nR ? (double)x[u] - cR : 0.0;
-            m[2] += e;
-            m[3] += e * e;
-          }
+        for (int x = 0; x < 4; ++x) m[x] = (sh.mom[0][x] + sh.mom[1][x]) + (sh.mom[2][x] + sh.mom[3][x]);
+      }
+      if (!resident && sums_A) {     // the state's sums, and the in-loop appends on top (every thread the same)
+        m[0] = mom_pre[0];
+        m[1] = mom_pre[1];
+        for (int j = 0; j < ne; ++j) {
+          const double e = (double)sh.extra[j] - cA;
+          m[0] += e;
+          m[1] += e * e;
         }
       }
-#pragma unroll
-      for (int x = 0; x < 4; ++x) {
-        m[x] = half_sum_d(m[x]);
-        m[x] += __shfl_xor(m[x], 32);
+      if (!resident && sums_R) {
+        m[2] = mom_pre[2];
+        m[3] = mom_pre[3];
       }
-      if (lane == 0) {
-#pragma unroll
-        for (int x = 0; x < 4; ++x) sh.mom[wave][x] = m[x];
-      }
-      __syncthreads();
-#pragma unroll
-      for (int x = 0; x < 4; ++x) m[x] = (sh.mom[0][x] + sh.mom[1][x]) + (sh.mom[2][x] + sh.mom[3][x]);
       Kde kA, kR;
       if (kde_constants(m[0], m[1], n_i, nR, a.bw_rule, &kA) && kde_constants(m[2], m[3], nR, n_i, a.bw_rule, &kR)) {
         double ja, jr;

@@ -12,6 +12,7 @@
 namespace adasd {
 
 constexpr int kWideCap = 512;       // list capacity from which the decision stage is launched with a workgroup per position
+constexpr int kSumsMin = 4096;      // list length from which the state's running sums are kept and used
 constexpr int kWideMin = 384;       // list length from which a sequence actually uses them
 constexpr int kMaxSplit = 64;        // vocabulary slices per row (statistics kernels)
 constexpr int kMaxSampleSplit = 128; // vocabulary slices per sequence (sampling kernel)
@@ -116,6 +117,7 @@ struct UpdateArgs {
   float* LR;
   int32_t* nA;
   int32_t* nR;
+  double* mom;          // [B,4] running sums of the lists about their first elements, or null
   const int32_t* n_accept;
   const int32_t* draft_len;
   const float* H_q;
@@ -134,6 +136,7 @@ struct DecideArgs {
   const float* LR;
   const int32_t* nA;
   const int32_t* nR;
+  const double* mom;    // [B,4] running sums of the lists about their first elements, or null: add them up here
   uint32_t seed_lo, seed_hi;
   const uint32_t* seq_id;
   const uint32_t* round;
@@ -187,7 +190,9 @@ hipError_t launch_shard_settle(const SampleArgs& a, int G, float* tau, const voi
 hipError_t launch_sample(const SampleArgs& a, int S, const Workspace& ws, hipStream_t st);
 
 hipError_t launch_update(const UpdateArgs& a, hipStream_t st);
+hipError_t launch_state_refresh(const UpdateArgs& a, hipStream_t st);
 hipError_t launch_state_init(const UpdateArgs& a, hipStream_t st);
+hipError_t launch_state_refresh(const UpdateArgs& a, hipStream_t st);
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t st);
 
 }  // namespace adasd

@@ -886,6 +886,49 @@ def test_update_matches_oracle_and_state_round_trip(am, wl, oracle, B, K, cap):
     assert (host["nA"] == cap).any()          # overflow was exercised
 
 
+def test_running_sums_of_long_lists_follow_every_update(am, wl, oracle):
+    """adasd_state.mom: from 4096 samples on, the sums of a list are kept by the update step (added up from
+    scratch in the call that crosses the mark) and equal the sums recomputed from the list; a state without
+    running sums (the decision stage adds the lists up itself) gives the same decisions."""
+    B, K, V, cap = 6, 7, 4096, 4130
+    g = torch.Generator().manual_seed(8)
+    host = wl.threshold_state(B, cap, g, n_hist=4080)            # sixteen samples short of the mark
+    host["nA"][1] = 4096; host["nR"][1] = 4096                   # already there (refresh makes the sums)
+    host["nA"][2] = 100; host["nR"][2] = 4095                    # a short accepted list stays without sums
+    host["nA"][3] = cap - 3                                      # overflows: dropped appends are not summed
+    host["LA"][:, 4080:] = host["LA"][:, :cap - 4080]
+    host["LR"][:, 4080:] = host["LR"][:, :cap - 4080]
+    st = am.State(B, cap).load(host)
+    plain = am.State(B, cap, running_sums=False).load(host)
+    ws = am.Workspace(B, K, V, torch.bfloat16)
+    src = wl.ClosedLoopSource(B, V, K, dtype=torch.bfloat16, seed=5)
+    crossed = set()
+    for rnd in range(9):
+        t, d, x = src.next_round()
+        outs = []
+        for state in (st, plain):
+            outs.append(am.verify(t.cuda(), d.cuda(), x.cuda(), ws, state=state, seed=3, round0=rnd,
+                                  options=am.Options(apply_update=1 if rnd % 2 else 0)))
+            if rnd % 2 == 0:
+                am.update_thresholds(state, K, outs[-1].n_accept, outs[-1].H_q, outs[-1].d_js)
+        torch.cuda.synchronize()
+        for name in ("n_accept", "next_token", "accept_mask"):
+            assert torch.equal(getattr(outs[0], name), getattr(outs[1], name)), (rnd, name)
+        assert torch.allclose(outs[0].p_accept, outs[1].p_accept, rtol=0, atol=1e-6)
+        h = st.to_host()
+        mom = st.mom.cpu().numpy()
+        for b in range(B):
+            for which, (L, n) in enumerate((("LA", "nA"), ("LR", "nR"))):
+                cnt = int(h[n][b])
+                if cnt < 4096:
+                    continue
+                crossed.add((b, which))
+                v = h[L][b, :cnt].astype(np.float64)
+                want = [(v - v[0]).sum(), ((v - v[0]) ** 2).sum()]
+                assert np.allclose(mom[b, 2 * which:2 * which + 2], want, rtol=1e-12, atol=1e-15), (rnd, b, which)
+    assert len(crossed) >= 6 and (2, 0) not in crossed and h["nA"][3] == cap
+
+
 def test_verify_with_fused_update_matches_verify_then_update(am, wl, oracle):
     """options.apply_update: the decision kernel applies the round to the state; outputs and state must
     equal those of adasd_verify followed by adasd_update_thresholds, and the oracle's."""
