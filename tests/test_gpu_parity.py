@@ -325,7 +325,8 @@ def test_literal_variant_status_and_float64_path(am, wl, oracle):
 
 
 # ------------------------------------------------------------------------------- long histories
-@pytest.mark.parametrize("n_hist,cap", [(64, 512), (700, 1024), (5000, 5003), (40000, 40100)])
+@pytest.mark.parametrize("n_hist,cap", [(64, 512), (700, 1024), (5000, 5003), (40000, 40100), (64, 20000), (5000, 20000),
+                                        (17000, 20000)])
 @pytest.mark.parametrize("opt", [dict(), dict(list_update=1, base_test=1), dict(bw_rule=1, reject_rule=1)],
                          ids=["default", "literal", "scott-map"])
 def test_long_history_lists_take_the_workgroup_per_position_path(am, wl, oracle, n_hist, cap, opt, path):
