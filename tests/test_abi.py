@@ -75,6 +75,27 @@ def test_null_arguments_are_rejected_on_the_host(lib):
     assert lib.adasd_profile_read(0, None, None) == -1
 
 
+def test_newer_entry_points_validate_on_the_host(lib):
+    lib.adasd_state_refresh.argtypes = [C.c_void_p, C.c_void_p]
+    assert lib.adasd_state_refresh(None, None) == -1
+    lib.adasd_draft_step.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int64, C.c_void_p, C.c_void_p,
+                                     C.c_int, C.c_int, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint32,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                     C.c_void_p]
+    args = [None, 1, 4, 128, 128, None, None, 0, 20, 7, None, None, 0, None, None, None, None, None, 0, None]
+    assert lib.adasd_draft_step(*args) == -1                    # no logits
+    args[2] = 0
+    assert lib.adasd_draft_step(*args) == 0                     # no rows: nothing to do
+    for name, n_ptr in (("stats", 1), ("jsd", 2), ("sample", 1), ("pick", 2), ("settle", 2)):
+        f = getattr(lib, "adasd_verify_shard_" + name)
+        f.argtypes = [C.c_void_p] * (3 + n_ptr)
+        assert f(*([None] * (3 + n_ptr))) == -1, name
+    lib.adasd_verify_shard_decide.argtypes = [C.c_void_p] * 6
+    assert lib.adasd_verify_shard_decide(None, None, None, None, None, None) == -1
+    lib.adasd_verify_shard_refine.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+    assert lib.adasd_verify_shard_refine(None, None, None, 0, None, None) == -1
+
+
 def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     import paper_2512_11280_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)
