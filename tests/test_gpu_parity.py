@@ -325,14 +325,13 @@ def test_literal_variant_status_and_float64_path(am, wl, oracle):
 
 
 # ------------------------------------------------------------------------------- long histories
-@pytest.mark.parametrize("n_hist,cap", [(64, 512), (700, 1024), (5000, 5003), (40000, 40100), (64, 20000), (5000, 20000),
-                                        (17000, 20000)])
+@pytest.mark.parametrize("n_hist,cap,path", [(64, 512, 1), (700, 1024, 1), (700, 1024, 2), (5000, 5003, 1), (40000, 40100, 1),
+                                             (64, 20000, 1), (5000, 20000, 1), (17000, 20000, 1)])
 @pytest.mark.parametrize("opt", [dict(), dict(list_update=1, base_test=1), dict(bw_rule=1, reject_rule=1)],
                          ids=["default", "literal", "scott-map"])
 def test_long_history_lists_take_the_workgroup_per_position_path(am, wl, oracle, n_hist, cap, opt, path):
-    """From a list capacity of 512 on, the decision stage gives every position a workgroup of its own."""
-    if path == 2 and n_hist != 700:
-        pytest.skip("the statistics path does not matter here; one size covers it")
+    """From a list capacity of 512 on, the decision stage gives every position a workgroup of its own
+    (path: which statistics kernels ran before it)."""
     batch = wl.config_batched(B=5, k=6, V=8192, seed=300 + n_hist, cap=cap)
     g = torch.Generator().manual_seed(n_hist)
     batch.state = wl.threshold_state(batch.B, cap, g, n_hist=n_hist)
