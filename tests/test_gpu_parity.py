@@ -578,6 +578,40 @@ def test_column_sharded_draw_without_certain_mass_is_flagged(am, wl, oracle):
     assert st[1] == 0 and outs[0].next_token[1].item() == ref["next_token"][1]       # accepted: bonus token as usual
 
 
+def test_column_sharded_round_with_long_histories_and_without_drafts(am, wl, oracle):
+    cap = 600
+    batch = wl.config_batched(B=4, k=5, V=8192, seed=77, cap=cap)
+    g = torch.Generator().manual_seed(9)
+    batch.state = wl.threshold_state(batch.B, cap, g, n_hist=520)            # the per-position decision kernel
+    options = am.Options(base_test=1, list_update=1)
+    ctx = _sharded_decisions(am, batch, 3, options=options)
+    _sharded_tokens(am, batch, ctx, ctx[0])
+    rep = G.compare_verify(ctx[0][0], G.run_oracle(oracle, batch, options=options))
+    _report("sharded long history", rep)
+    # no drafted positions at all: only the bonus token is drawn
+    b0 = wl.VerifyBatch(batch.target[:, :1].contiguous(), batch.draft[:, :0].contiguous(),
+                        batch.draft_tokens[:, :0].contiguous(), None, wl.empty_state(batch.B, 8), batch.seed)
+    ctx0 = _sharded_decisions(am, b0, 2)
+    _sharded_tokens(am, b0, ctx0, ctx0[0])
+    ref0 = G.run_oracle(oracle, b0)
+    assert np.array_equal(ctx0[0][0].next_token.cpu().numpy(), ref0["next_token"])
+    assert (ctx0[0][0].n_accept == 0).all()
+
+
+def test_literal_variant_without_a_state(am, wl, oracle):
+    batch = wl.config_batched(B=4, k=5, V=8192, seed=78)
+    batch.state = {}
+    t, d, x = batch.target.cuda(), batch.draft.cuda(), batch.draft_tokens.cuda()
+    ws = am.Workspace(batch.B, batch.k, batch.V, torch.bfloat16)
+    options = am.Options(base_test=1, list_update=1)
+    out = am.verify(t, d, x, ws, seed=batch.seed, options=options)
+    torch.cuda.synchronize()
+    ref = oracle.verify(batch.target, batch.draft, x.cpu().numpy(), seed=batch.seed, base_test=1, list_update=1)
+    ref["posterior_at"] = lambda b, i, dd: 0.0
+    rep = G.compare_verify(out, ref)
+    assert rep["flips"] == 0 and (out.p_accept == 0).all()
+
+
 def test_column_sharded_argument_errors(am):
     ws = am.Workspace(2, 2, 64, torch.float32)
     t = torch.zeros(2, 3, 64, device="cuda")
