@@ -622,6 +622,42 @@ def test_column_sharded_argument_errors(am):
             am.verify_shard_stats(t[:, :, :40], d[:, :, :40], tok, ws, bad)
 
 
+# ------------------------------------------------------------------------------- seeded random shapes
+@pytest.mark.parametrize("case", range(48))
+def test_random_shapes_and_options(am, wl, oracle, case):
+    """Seeded draws of shape, dtype, lengths, history sizes and options: whatever combination comes up has
+    to meet the same bar."""
+    rng = np.random.default_rng(9000 + case)
+    B = int(rng.integers(1, 7))
+    K = int(rng.choice([1, 2, 3, 5, 8, 13, 20]))
+    V = int(rng.choice([9, 64, 257, 1000, 2048, 4099, 8200, 12345]))
+    dtype = torch.bfloat16 if rng.random() < 0.6 else torch.float32
+    cap = int(rng.choice([8, 40, 300, 600, 5000]))
+    n_hist = int(min(cap, rng.choice([0, 1, 2, 30, 200, 450, 4200])))
+    batch = wl.config_batched(B=B, k=K, V=V, seed=1000 + case, dtype=dtype, cap=64)
+    g = torch.Generator().manual_seed(case)
+    st = wl.threshold_state(B, cap, g, n_hist=max(n_hist, 1))
+    st["nA"][:] = np.minimum(n_hist, rng.integers(0, n_hist + 1, B) + n_hist // 2)
+    st["nR"][:] = np.minimum(n_hist, rng.integers(0, n_hist + 1, B) + n_hist // 2)
+    batch.state = st
+    if rng.random() < 0.5:
+        batch.draft_len = torch.tensor(rng.integers(0, K + 1, B), dtype=torch.int32)
+    if rng.random() < 0.3:
+        batch.draft_tokens[rng.integers(0, B), rng.integers(0, K)] = V + 3        # a broken token
+    if rng.random() < 0.3:
+        batch.target[rng.integers(0, B), rng.integers(0, K + 1), : V // 2] = float("-inf")
+    opt = dict(base_test=int(rng.integers(0, 2)), list_update=int(rng.integers(0, 2)),
+               reject_rule=int(rng.integers(0, 2)), bw_rule=int(rng.integers(0, 2)),
+               apply_update=int(rng.integers(0, 2)), kde_min_n=int(rng.choice([0, 2, 5])))
+    options = am.Options(**opt)
+    seq_id = rng.integers(0, 2 ** 32, B, dtype=np.uint64).astype(np.uint32)
+    out, _, _ = G.run_gpu(am, batch, options=options, seq_id=seq_id, stats_path=int(rng.integers(1, 3)))
+    ref = G.run_oracle(oracle, batch, options=options, seq_id=seq_id)
+    rep = G.compare_verify(out, ref, info_bits=16 | 8)
+    print(f"[random {case}] B={B} K={K} V={V} {dtype} cap={cap} n={n_hist} {opt}: flips={rep['flips']}", flush=True)
+    assert rep["flips"] <= 1
+
+
 # ------------------------------------------------------------------------------- close calls of the argmax
 @pytest.mark.parametrize("dtype,V", [(torch.bfloat16, 4104), (torch.float32, 2056), (torch.bfloat16, 4107)],
                          ids=["bf16-2slices", "f32-2slices", "bf16-unaligned"])
