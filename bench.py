@@ -202,6 +202,27 @@ def main():
     draft_step_kernels_us = ms / 200 * 1e3 if n else None
     am.profile_disable()
 
+    # ---- practical ceiling: the same logits streamed by a kernel that does no arithmetic (one 32 KiB
+    #      piece per workgroup, all loads of a thread in flight at once), rotating over the input sets
+    #      (one launch per set over a contiguous copy of exactly the rows the statistics stage reads)
+    copies = [torch.cat([t[:, :K].reshape(-1), d.reshape(-1)]) for t, d, _, _ in sets]
+    sink = torch.empty(copies[0].numel() * 2 // 32768 + 1, dtype=torch.int32, device="cuda")
+    reps_stream = 40
+    for c in copies:
+        am.stream_read(c, sink)
+    torch.cuda.synchronize()
+    am.profile_enable(reps_stream + 8)
+    stream_bytes = 0
+    for i in range(reps_stream):
+        c = copies[i % len(copies)]
+        am.stream_read(c, sink)
+        stream_bytes += c.numel() * c.element_size()
+    torch.cuda.synchronize()
+    ms, n = am.profile_read(6)
+    am.profile_disable()
+    stream_gbps = stream_bytes / (ms * 1e-3) / 1e9 if n and ms > 0 else None
+    del copies
+
     # ---- one holder's share of the column-sharded path (its V/G columns, the replicated stages in full)
     sharded = None
     if args.shards > 0:
@@ -286,7 +307,9 @@ def main():
                      "kernel": "k_stats_pipe + k_stats_finish" if "jsd" not in kern_us else "k_rowstats + k_jsd",
                      "algorithmic_bytes": algo_bytes,
                      "kernel_us": stats_us,
-                     "per_kernel": per_kernel},
+                     "per_kernel": per_kernel,
+                     "stream_read": {"GBps": stream_gbps, "frac": stream_gbps / HBM_PEAK_GBS if stream_gbps else None,
+                                     "what": "adasd_stream_read over the same logits: loads only, no arithmetic"}},
         "cpu_baseline": cpu,
         "kernel_us": kern_us,
         "draft_entropy_us_per_call": draft_us,

@@ -347,11 +347,24 @@ int adasd_update_thresholds(const adasd_state *st /* host */, int k_max, const i
  * adasd_profile_disable frees the events.  Kernel classes: 0 row statistics (normalisers + entropy;
  * with stats_path 2 the single-read kernel and its finalisation, class 1 then stays empty),
  * 1 JS distance (two-kernel path), 2 decision, 3 token sampling, 4 state update, 5 drafting calls
- * (adasd_draft_entropy and adasd_draft_step: one kernel per call).
+ * (adasd_draft_entropy and adasd_draft_step: one kernel per call), 6 adasd_stream_read.
  */
 int adasd_profile_enable(int max_launches);
 int adasd_profile_read(int kernel_class, double *total_ms /* host */, int *launches /* host */);
 int adasd_profile_disable(void);
+
+/*
+ * Diagnostics for benchmarks: reads `bytes` bytes of device memory at `src` once, with 128-bit loads
+ * in the launch shape of the statistics kernels (one workgroup per 32 KiB), and does nothing with them
+ * beyond folding them into one word per workgroup, written to sink[0 .. ceil(bytes / 32768)).  Its
+ * duration (kernel class 6) is the rate at which the chip streams logits to a kernel without
+ * arithmetic: the practical ceiling beside which the bandwidth of the statistics kernels (Appendix A
+ * and Section 2.2 of the paper: entropy and JS distance over the whole vocabulary) is read.
+ * src: device, 16-byte aligned, bytes a multiple of 16 (else ADASD_ERR_MISALIGNED); sink: device,
+ * caller-owned, sink_words >= ceil(bytes / 32768) (else ADASD_ERR_WORKSPACE); bytes == 0
+ * does nothing.  Enqueues one kernel on `stream`; allocates nothing and does not synchronise.
+ */
+int adasd_stream_read(const void *src, size_t bytes, uint32_t *sink, size_t sink_words, void *stream);
 
 /*
  * Test hook for the bounded waits of the single-read statistics kernel (stats_path 2): a workgroup

@@ -99,6 +99,7 @@ def load_library():
     L.adasd_update_thresholds.argtypes = [C.POINTER(_State), C.c_int, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.POINTER(_Options), C.c_void_p,
                                           C.c_void_p]
+    L.adasd_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p]
     L.adasd_profile_enable.argtypes = [C.c_int]
     L.adasd_profile_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     _lib = L
@@ -485,6 +486,16 @@ def update_thresholds(state: State, k_max: int, n_accept: torch.Tensor, H_q: tor
         C.byref(st), k_max, n_accept.data_ptr(), _p(draft_len), H_q.data_ptr(), d_js.data_ptr(),
         C.byref(opt) if opt is not None else None, _p(status), _stream())
     _check(rc, "adasd_update_thresholds")
+
+
+def stream_read(src: torch.Tensor, sink: torch.Tensor):
+    """adasd_stream_read on a contiguous device tensor; sink: int32 device tensor, one word per 32 KiB."""
+    if not src.is_contiguous():
+        raise ValueError("src must be contiguous")
+    _need(sink, torch.int32, "sink")
+    rc = load_library().adasd_stream_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(),
+                                          sink.numel(), _stream())
+    _check(rc, "adasd_stream_read")
 
 
 def set_spin_limit(polls: int):

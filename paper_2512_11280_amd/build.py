@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libadasd.so")
-SOURCES = ["stats.hip", "stats_fused.hip", "decide.hip", "sample.hip", "draft.hip", "shard.hip", "api.hip"]
+SOURCES = ["stats.hip", "stats_fused.hip", "decide.hip", "sample.hip", "draft.hip", "shard.hip", "diag.hip", "api.hip"]
 HEADERS = [os.path.join(CSRC, h) for h in ("device_common.h", "internal.h", "decide_device.h",
                                              "sample_device.h", "stats_device.h")] + [
            os.path.join(os.path.dirname(HERE), "include", "adasd.h")]

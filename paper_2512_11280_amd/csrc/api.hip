@@ -16,13 +16,13 @@ bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p
 std::atomic<int> g_spin_limit{1 << 16};
 
 // ---- optional kernel timing ----------------------------------------------------------------
-constexpr int kClasses = 6;
+constexpr int kClasses = 7;
 struct Profiler {
   std::mutex mu;
   bool on = false;
   int cap = 0;
   std::vector<hipEvent_t> start[kClasses], stop[kClasses];
-  int used[kClasses] = {0, 0, 0, 0, 0, 0};
+  int used[kClasses] = {0, 0, 0, 0, 0, 0, 0};
 } g_prof;
 
 thread_local int t_class = -1;   // kernel class of the timing scope that is open on this thread
@@ -613,6 +613,18 @@ int adasd_set_spin_limit(int polls) {
   if (polls < 0) return ADASD_ERR_INVALID_ARG;
   g_spin_limit.store(polls);
   return ADASD_OK;
+}
+
+int adasd_stream_read(const void* src, size_t bytes, uint32_t* sink, size_t sink_words, void* stream) {
+  if (bytes == 0) return ADASD_OK;
+  if (!src || !sink) return ADASD_ERR_INVALID_ARG;
+  if (!aligned_to(src, 16) || (bytes & 15) != 0 || !aligned_to(sink, 4)) return ADASD_ERR_MISALIGNED;
+  const size_t groups = stream_read_groups(bytes);
+  if (groups > 0x7fffffffu) return ADASD_ERR_CAPACITY;
+  if (sink_words < groups) return ADASD_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  Scope sc(6, s);
+  return launch_stream_read(src, bytes, sink, s) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
 }
 
 int adasd_profile_enable(int max_launches) {

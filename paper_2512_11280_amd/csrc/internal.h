@@ -103,6 +103,10 @@ inline void launch_kernel(Kernel kernel, dim3 grid, dim3 block, hipStream_t st, 
 
 int pick_split(int rows, int V, int dt);
 
+// plain streaming read (diagnostics): one word per workgroup goes to `sink`
+size_t stream_read_groups(size_t bytes);
+hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t st);
+
 hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Workspace& ws, hipStream_t st);
 bool fused_plan(const RowMap& map, int dt, int* NV_out, int* S_out);
 hipError_t launch_stats_fused(const RowMap& map, int dt, int NV, int S, int spin_limit,

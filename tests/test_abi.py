@@ -92,6 +92,12 @@ def test_newer_entry_points_validate_on_the_host(lib):
         assert f(*([None] * (3 + n_ptr))) == -1, name
     lib.adasd_verify_shard_decide.argtypes = [C.c_void_p] * 6
     assert lib.adasd_verify_shard_decide(None, None, None, None, None, None) == -1
+    lib.adasd_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p]
+    assert lib.adasd_stream_read(None, 0, None, 0, None) == 0          # nothing to read
+    assert lib.adasd_stream_read(None, 64, None, 1, None) == -1
+    assert lib.adasd_stream_read(256, 24, 256, 1, None) == -2            # not whole 128-bit vectors
+    assert lib.adasd_stream_read(264, 64, 256, 1, None) == -2            # source below 16-byte alignment
+    assert lib.adasd_stream_read(256, 65536, 256, 1, None) == -4         # two pieces, one word of room
     lib.adasd_verify_shard_refine.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
     assert lib.adasd_verify_shard_refine(None, None, None, 0, None, None) == -1
 

@@ -1166,6 +1166,24 @@ def test_verify_and_draft_step_replay_from_a_hip_graph(am, wl):
                 assert torch.equal(torch.nan_to_num(got[k].double(), nan=-7.0), torch.nan_to_num(v.double(), nan=-7.0)), (i, k)
 
 
+@pytest.mark.parametrize("n_bytes", [16, 32768, 32768 + 16, 5 * 32768 - 4096, 131334144 // 8])
+def test_stream_read_touches_every_byte_once(am, n_bytes):
+    """The diagnostic read leaves the xor of every 32-bit word of each 32 KiB piece: integer work, exact."""
+    g = torch.Generator().manual_seed(n_bytes)
+    host = torch.randint(-2**31, 2**31 - 1, (n_bytes // 4,), dtype=torch.int32, generator=g)
+    pieces = (n_bytes + 32767) // 32768
+    sink = torch.full((pieces + 2,), 0x5a5a5a5a, dtype=torch.int32, device="cuda")
+    am.stream_read(host.cuda(), sink)
+    torch.cuda.synchronize()
+    got = sink.cpu().numpy()
+    words = host.numpy()
+    want = [int(np.bitwise_xor.reduce(words[p * 8192:(p + 1) * 8192])) for p in range(pieces)]
+    assert got[:pieces].tolist() == want
+    assert (got[pieces:] == 0x5a5a5a5a).all()           # nothing written past the last piece
+    with pytest.raises(am.AdasdError):
+        am.stream_read(host.cuda(), sink[:pieces - 1] if pieces > 1 else sink[:0])
+
+
 def test_bounded_wait_expiry_gives_identical_results(am, wl):
     """With a spin limit of 0 every workgroup of the single-read kernel stops waiting at once and
     recomputes the other slices' results itself; the outputs must not change by a single bit."""
