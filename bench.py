@@ -26,8 +26,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # under profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a plain copy of known
 # size): k_rowstats 131.63 MB + 0.13 MB, k_jsd 132.94 MB + 0.08 MB.  Only valid for the default path.
 STAGE_TRAFFIC_BYTES = 264.78e6
-B, K, V = 32, 8, 128256
-N_SETS = 4                     # 4 x 139.5 MB of logits
+# shapes: the headline workload is the one the metric is quoted on; "large" is a side measurement
+WORKLOADS = {"headline": (32, 8, 128256, 4),      # 4 sets x 139.5 MB of logits
+             "large": (128, 16, 152064, 2)}       # 2 sets x 1.28 GB
 LIST_CAP = 8192
 
 
@@ -37,7 +38,10 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--sets", type=int, default=N_SETS)
+    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="headline",
+                    help="headline: B=32 k=8 V=128256 (the metric's workload); large: B=128 k=16 V=152064 "
+                         "(side measurement, no CPU baseline, no counter-derived traffic figure)")
+    ap.add_argument("--sets", type=int, default=0, help="rotating input sets (0: the workload's default)")
     ap.add_argument("--stats-path", type=int, default=0, help="0 library default, 1 two-kernel path, 2 single-read kernel")
     ap.add_argument("--separate-update", action="store_true",
                     help="apply the update step with a separate adasd_update_thresholds call")
@@ -60,6 +64,11 @@ def main():
         sys.exit("bench.py: this build runs on exactly one GPU (sequences are independent, so the "
                  "path shards by sequence with no communication); use --gpus 1")
 
+    B, K, V, n_sets = WORKLOADS[args.workload]
+    large = args.workload == "large"
+    if args.sets > 0:
+        n_sets = args.sets
+
     import numpy as np
     import torch
 
@@ -73,8 +82,12 @@ def main():
     # ---- seeded synthetic inputs, resident in HBM before any timing
     sets = []
     host0 = None
-    for i in range(args.sets):
-        batch = wl.config_batched(seed=wl.DEFAULT_SEED + 2 + 100 * i, B=B, k=K, V=V, cap=LIST_CAP)
+    for i in range(n_sets):
+        if large:
+            batch = wl.config_large(seed=wl.DEFAULT_SEED + 3 + 100 * i, B=B, k=K, V=V, cap=LIST_CAP)
+            print(f"input set {i} generated", file=sys.stderr, flush=True)
+        else:
+            batch = wl.config_batched(seed=wl.DEFAULT_SEED + 2 + 100 * i, B=B, k=K, V=V, cap=LIST_CAP)
         if i == 0:
             host0 = batch
         sets.append((batch.target.cuda(), batch.draft.cuda(), batch.draft_tokens.cuda(), batch.seed))
@@ -265,7 +278,7 @@ def main():
 
     # ---- CPU oracle on the same workload (baseline, not a target)
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not large:
         from oracle import load_oracle
         ora = load_oracle()
         s = host0.state
@@ -303,7 +316,7 @@ def main():
                                else "defaults (ratio test + residual, lists as of the round's start)"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": STAGE_TRAFFIC_BYTES if ("jsd" in kern_us and args.stats_path in (0, 1)) else None,
+                     "traffic": STAGE_TRAFFIC_BYTES if ("jsd" in kern_us and args.stats_path in (0, 1) and not large) else None,
                      "kernel": "k_stats_pipe + k_stats_finish" if "jsd" not in kern_us else "k_rowstats + k_jsd",
                      "algorithmic_bytes": algo_bytes,
                      "kernel_us": stats_us,
