@@ -13,7 +13,7 @@ __global__ void __launch_bounds__(kBlock) k_decide(DecideArgs a, UpdateArgs upd,
   __shared__ DecideShared sh;
   decide_sequence<DT, INLOOP>(a, ws, blockIdx.x, sh);
   // the round applied to the state right away (the lists were only read above)
-  if (upd.B > 0 && threadIdx.x < 64) update_sequence(upd, blockIdx.x, threadIdx.x, sh.first_reject, sh.k_b);
+  if (upd.B > 0 && threadIdx.x < 64) update_sequence_shared(upd, blockIdx.x, threadIdx.x, sh.first_reject, sh.k_b, sh);
 }
 
 // Long histories: one workgroup per candidate position.  The workgroup of position 0 does all the work of
@@ -33,7 +33,7 @@ __global__ void __launch_bounds__(kBlock) k_decide_wide(DecideArgs a, UpdateArgs
   if (n_long < kWideMin) {
     if (pos != 0) return;
     decide_sequence<DT, INLOOP>(a, ws, b, sh);
-    if (upd.B > 0 && threadIdx.x < 64) update_sequence(upd, b, threadIdx.x, sh.first_reject, sh.k_b);
+    if (upd.B > 0 && threadIdx.x < 64) update_sequence_shared(upd, b, threadIdx.x, sh.first_reject, sh.k_b, sh);
     return;
   }
   decide_position_wide<DT, INLOOP>(a, upd, ws, ws.pos_rec, b, pos, sh, wsh);

@@ -94,7 +94,9 @@ struct DecideShared {
   double lse2[ADASD_MAX_K][2];      // normalisers of the candidate positions (for the sampling plan)
   uint8_t acc[ADASD_MAX_K];         // 1: position accepted
   uint8_t bad[ADASD_MAX_K];
-  float dist[ADASD_MAX_K];          // in-loop appends: the round's distances
+  float dist[ADASD_MAX_K];          // the round's distances (in-loop appends; the fused update step)
+  float hq[ADASD_MAX_K];            // the round's draft entropies (the fused update step)
+  float la[kNarrowMax], lr[kNarrowMax];   // both lists, staged while their moments are formed
   uint32_t status;
 };
 
@@ -175,14 +177,10 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
   const uint32_t seq = a.seq_id ? a.seq_id[b] : (uint32_t)b;
   const uint32_t rnd = a.round ? a.round[b] : a.round0;
 
-  // The first position of each group is requested before the list moments are formed, so the two
-  // chains of dependent loads (token -> its logits, list lengths -> samples) run side by side.
-  auto load_pos = [&](int i) { return load_position<DT>(a, ws, b, i, rnd, seq); };
-  PosLoad first;
-  if (grp < kb) first = load_pos(grp);
-
-  // ---- Bayesian test set-up: both lists need enough samples and spread (else P(A|d) = 0).
-  // One pass over both lists (moments about the first element), one workgroup reduction.
+  // Two chains of dependent loads run side by side: list lengths -> samples and token -> its logits.
+  // The lengths are asked for first, then the first position of each group (its token, and once that
+  // is back its two logits), then the samples: a wavefront issues in order, so whatever stands behind
+  // the wait for the token must not be the start of the other chain.
   const int min_n = a.kde_min_n < 2 ? 2 : a.kde_min_n;
   int nA = 0, nR = 0;
   const float* LA = nullptr;
@@ -193,6 +191,13 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
     LA = a.LA + (size_t)b * a.cap;
     LR = a.LR + (size_t)b * a.cap;
   }
+  auto load_pos = [&](int i) { return load_position<DT>(a, ws, b, i, rnd, seq); };
+  PosLoad first;
+  if (grp < kb) first = load_pos(grp);
+
+  // ---- Bayesian test set-up: both lists need enough samples and spread (else P(A|d) = 0).
+  // One pass over both lists (moments about the first element), one workgroup reduction; the samples
+  // stay in shared memory for the kernel sums of the positions.
   int n_room = 0;        // in-loop appends the list can still take
   if (INLOOP) {
     // All distances of the round first: the groups fold them, one wavefront ranks those that pass.
@@ -220,7 +225,8 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
     __syncthreads();
     n_room = LA ? max(a.cap - nA, 0) : 0;
   }
-  bool kde_on = !a.relaxed_off && nR >= min_n && (INLOOP ? (LA != nullptr && nA + n_room >= min_n) : nA >= min_n);
+  // (no positions, no test: the launch sends lists of kNarrowMax samples or more to the other form unless k_max is 0)
+  bool kde_on = K > 0 && !a.relaxed_off && nR >= min_n && (INLOOP ? (LA != nullptr && nA + n_room >= min_n) : nA >= min_n);
   Kde kA, kR;
   double cA = 0.0, cR = 0.0;
   double m[4] = {0.0, 0.0, 0.0, 0.0};
@@ -229,12 +235,16 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
     cR = (double)LR[0];
     // (lists this short never have running sums in the state: they are added up here)
     for (int j = tid; j < nA; j += kBlock) {
-      const double e = (double)LA[j] - cA;
+      const float v = LA[j];
+      if (j < kNarrowMax) sh.la[j] = v;
+      const double e = (double)v - cA;
       m[0] += e;
       m[1] += e * e;
     }
     for (int j = tid; j < nR; j += kBlock) {
-      const double e = (double)LR[j] - cR;
+      const float v = LR[j];
+      if (j < kNarrowMax) sh.lr[j] = v;
+      const double e = (double)v - cR;
       m[2] += e;
       m[3] += e * e;
     }
@@ -247,7 +257,7 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
 #pragma unroll
       for (int x = 0; x < 4; ++x) sh.mom[wave][x] = m[x];
     }
-    __syncthreads();
+    __syncthreads();     // (also: the staged samples are in place)
 #pragma unroll
     for (int x = 0; x < 4; ++x) m[x] = (sh.mom[0][x] + sh.mom[1][x]) + (sh.mom[2][x] + sh.mom[3][x]);
     if (!INLOOP) {
@@ -281,11 +291,17 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
       d = (double)sh.dist[i];
     } else if (a.jsd_split > 0) {
       const float d_out = fold_distance(L);
-      if (l32 == 0) a.d_js[o] = d_out;
+      if (l32 == 0) {
+        a.d_js[o] = d_out;
+        sh.dist[i] = d_out;
+      }
       d = (double)d_out;
     } else {
-      d = (double)a.d_js[o];
+      const float d_in = a.d_js[o];
+      if (l32 == 0) sh.dist[i] = bad ? NAN : d_in;
+      d = (double)d_in;
     }
+    if (l32 == 0) sh.hq[i] = bad ? NAN : rq.H;
     double PA = 0.0;
     if (INLOOP) {
       if (!bad && kde_on) {
@@ -299,14 +315,14 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
         }
         if (n_i >= min_n && kde_constants(s1, s2, n_i, nR, a.bw_rule, &kA) &&
             kde_constants(m[2], m[3], nR, n_i, a.bw_rule, &kR)) {
-          double ja = half_log_joint_ext(d, LA, nA, sh.extra, ne, kA);
-          double jr = half_log_joint(d, LR, nR, kR);
+          double ja = half_log_joint_ext(d, sh.la, nA, sh.extra, ne, kA);
+          double jr = half_log_joint(d, sh.lr, nR, kR);
           PA = 1.0 / (1.0 + (double)ex2((float)((jr - ja) * 1.44269504088896340736)));
         }
       }
     } else if (!bad && kde_on) {
-      double ja = half_log_joint(d, LA, nA, kA);
-      double jr = half_log_joint(d, LR, nR, kR);
+      double ja = half_log_joint(d, sh.la, nA, kA);
+      double jr = half_log_joint(d, sh.lr, nR, kR);
       PA = 1.0 / (1.0 + (double)ex2((float)((jr - ja) * 1.44269504088896340736)));
     }
     if (l32 != 0) continue;
@@ -392,6 +408,8 @@ namespace adasd {
 // d: the lane's distance (lanes <= r, below kb), H: the draft entropy of the rejected position (lane r).
 __device__ inline void update_sequence_core(const UpdateArgs& a, int b, int lane, int r, int kb, float d, float H) {
   const int nA = a.nA[b], nR = a.nR[b];
+  double ent_sum = a.ent_sum[b];      // (asked for with the lengths: the last lane needs them at the very end)
+  int ent_cnt = a.ent_cnt[b];
   const float lo = a.d_eps, hi = 1.0f - a.d_eps;
   if (!(lane <= r && lane < kb)) d = 0.f;
   const bool pass = d > lo && d < hi;                       // NaN fails both comparisons
@@ -469,8 +487,10 @@ __device__ inline void update_sequence_core(const UpdateArgs& a, int b, int lane
   int nR_new = nR;
   if (r < kb) {
     if (isfinite(H)) {
-      a.ent_sum[b] += (double)H;
-      a.ent_cnt[b] += 1;
+      ent_sum += (double)H;
+      ent_cnt += 1;
+      a.ent_sum[b] = ent_sum;
+      a.ent_cnt[b] = ent_cnt;
     }
     if (pass) {
       if (nR < a.cap) a.LR[(size_t)b * a.cap + nR_new++] = d;
@@ -479,9 +499,18 @@ __device__ inline void update_sequence_core(const UpdateArgs& a, int b, int lane
   }
   a.nA[b] = nA_new;
   a.nR[b] = nR_new;
-  const int cnt = a.ent_cnt[b];
-  a.T_G[b] = cnt > 0 ? (float)(a.ent_sum[b] / (double)cnt) : 0.f;
+  a.T_G[b] = ent_cnt > 0 ? (float)(ent_sum / (double)ent_cnt) : 0.f;
   if (a.status && st) a.status[b] |= st;
+}
+
+// The update step right after the decisions of the same workgroup: distances and entropies as that
+// left them in shared memory (the values it wrote to d_js / H_q).
+__device__ inline void update_sequence_shared(const UpdateArgs& a, int b, int lane, int r, int kb,
+                                              const DecideShared& sh) {
+  float d = 0.f, H = 0.f;
+  if (lane <= r && lane < kb) d = sh.dist[lane];
+  if (lane == r && r < kb) H = sh.hq[r];
+  update_sequence_core(a, b, lane, r, kb, d, H);
 }
 
 __device__ inline void update_sequence(const UpdateArgs& a, int b, int lane, int r, int kb) {

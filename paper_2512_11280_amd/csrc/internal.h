@@ -14,6 +14,7 @@ namespace adasd {
 constexpr int kWideCap = 512;       // list capacity from which the decision stage is launched with a workgroup per position
 constexpr int kSumsMin = 4096;      // list length from which the state's running sums are kept and used
 constexpr int kWideMin = 384;       // list length from which a sequence actually uses them
+constexpr int kNarrowMax = kWideCap; // so the one-workgroup form never sees a longer list: it stages both in shared memory
 constexpr int kMaxSplit = 64;        // vocabulary slices per row (statistics kernels)
 constexpr int kMaxSampleSplit = 128; // vocabulary slices per sequence (sampling kernel)
 constexpr int kMaxFusedSplit = 128;  // wavefront slices per row pair in the fused statistics kernel
