@@ -411,7 +411,7 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   const UpdateArgs& upd = v.upd;
   const int B = a->B, K = a->k_max, V = a->V;
   hipStream_t st = (hipStream_t)stream;
-  VerifyOut vout{a->H_p, a->H_q, a->d_js};
+  VerifyOut vout{a->H_p, a->H_q, a->d_js, nullptr, nullptr};
   int fNV = 0, fS = 0;
   if (K > 0 && opt.stats_path == 2 && fused_plan(map, (int)a->dt, &fNV, &fS)) {
     Scope sc(0, st);
@@ -425,9 +425,12 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
     }
     {
       Scope sc(1, st);
+      vout.tokens = a->draft_tokens;
+      vout.tok = a->draft_tokens ? ws.tok : nullptr;
       if (launch_jsd(map, (int)a->dt, S, S, ws, vout, st) != hipSuccess) return ADASD_ERR_HIP;
     }
     d.jsd_split = S;
+    d.tok = vout.tok;
   }
   {
     Scope sc(2, st);

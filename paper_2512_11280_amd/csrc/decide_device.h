@@ -121,7 +121,7 @@ __device__ __forceinline__ PosLoad load_position(const DecideArgs& a, const Work
       ((int64_t)b * a.map.seq_stride[0] + (int64_t)i * a.map.pos_stride[0]) * Elem<DT>::bytes;
   const char* qrow = a.map.base[1] +
       ((int64_t)b * a.map.seq_stride[1] + (int64_t)i * a.map.pos_stride[1]) * Elem<DT>::bytes;
-  if (a.tok) {            // column-sharded call: the owning shard looked the two logits up
+  if (a.tok) {            // looked up already (by the JS kernel, or by the shard that owns the column)
     const float2 z = a.tok[o];
     L.zp = z.x;
     L.zq = z.y;
@@ -177,10 +177,10 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
   const uint32_t seq = a.seq_id ? a.seq_id[b] : (uint32_t)b;
   const uint32_t rnd = a.round ? a.round[b] : a.round0;
 
-  // Two chains of dependent loads run side by side: list lengths -> samples and token -> its logits.
-  // The lengths are asked for first, then the first position of each group (its token, and once that
-  // is back its two logits), then the samples: a wavefront issues in order, so whatever stands behind
-  // the wait for the token must not be the start of the other chain.
+  // Two chains of dependent loads run side by side: list lengths -> samples and, where the token's
+  // logits were not looked up beforehand, token -> its logits.  The lengths are asked for first, then
+  // the first position of each group, then the samples: a wavefront issues in order, so whatever
+  // stands behind the wait for the token must not be the start of the other chain.
   const int min_n = a.kde_min_n < 2 ? 2 : a.kde_min_n;
   int nA = 0, nR = 0;
   const float* LA = nullptr;

@@ -53,6 +53,16 @@ template <int DT> __device__ __forceinline__ float load_elem(const char* row, in
   return reinterpret_cast<const float*>(row)[v];
 }
 
+// The same in two steps, for a load whose value is only needed much later: the bits now, the float then
+// (the wait for the load stands where the bits are first used).
+template <int DT> __device__ __forceinline__ uint32_t load_elem_bits(const char* row, int64_t v) {
+  if (DT == ADASD_BF16) return (uint32_t)reinterpret_cast<const uint16_t*>(row)[v];
+  return reinterpret_cast<const uint32_t*>(row)[v];
+}
+template <int DT> __device__ __forceinline__ float elem_from_bits(uint32_t bits) {
+  return __uint_as_float(DT == ADASD_BF16 ? bits << 16 : bits);
+}
+
 // Unpack one 16-byte vector into Elem<DT>::per_vec floats (exact conversions).
 template <int DT> __device__ __forceinline__ void unpack(const uint4& q, float* z) {
   if (DT == ADASD_BF16) {

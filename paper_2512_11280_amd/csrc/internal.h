@@ -87,6 +87,10 @@ struct VerifyOut {
   float* H_p;
   float* H_q;
   float* d_js;
+  // With both set, the JS kernel also looks up the two logits of each position's drafted token and leaves
+  // them in tok[position], so the decision kernel does not start with a chain of two dependent loads.
+  const int32_t* tokens;   // [positions] or null
+  float2* tok;             // [positions] or null
 };
 
 // Kernel launches go through launch_kernel: while kernel timing is enabled and a timing scope is open,

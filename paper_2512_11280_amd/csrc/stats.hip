@@ -144,7 +144,13 @@ k_jsd(RowMap map, int S, int S_fold, Workspace ws, VerifyOut vout) {
       xq[j] = make_uint4(in ? b.x : neutral.x, in ? b.y : neutral.y, in ? b.z : neutral.z, in ? b.w : neutral.w);
     }
   };
-  // the first batch is requested before anything else: it does not depend on the normalisers
+  // The position's drafted token, for the look-up of its two logits further down (one thread per
+  // position).  Asked for ahead of the batch: loads come back in order, so the wait for the token then
+  // does not include the batch.
+  const bool gathers = s == 0 && tid == 0 && vout.tok != nullptr;
+  int x = -1;
+  if (gathers) x = vout.tokens[pos];
+  // the first batch is requested before anything else that waits: it does not depend on the normalisers
   if (vec_path && v0 < v1) load_batch(v0);
 
   // both rows' slice results are folded by every workgroup of the position, the same way
@@ -155,6 +161,11 @@ k_jsd(RowMap map, int S, int S_fold, Workspace ws, VerifyOut vout) {
   __syncthreads();
   const RowResult resp = sh_row[0], resq = sh_row[1];
   const bool bad = resp.bad || resq.bad;
+  uint32_t zx_p = 0u, zx_q = 0u;      // their bits: turned into floats where they are stored, at the very end
+  if (gathers && x >= 0 && x < V) {
+    zx_p = load_elem_bits<DT>(rp.ptr, x);
+    zx_q = load_elem_bits<DT>(rq.ptr, x);
+  }
   const float cp = (float)resp.lse2, cq = (float)resq.lse2;
   const float dc = (float)(resq.lse2 - resp.lse2);
   float acc = 0.f;
@@ -200,6 +211,10 @@ k_jsd(RowMap map, int S, int S_fold, Workspace ws, VerifyOut vout) {
       ws.rows[2 * pos + 1] = resq;
       if (vout.H_p) vout.H_p[pos] = resp.H;
       if (vout.H_q) vout.H_q[pos] = resq.H;
+      if (vout.tok) {
+        asm volatile("" : "+v"(zx_p), "+v"(zx_q));   // keeps the conversion, and with it the wait for the two loads, down here
+        vout.tok[pos] = make_float2(elem_from_bits<DT>(zx_p), elem_from_bits<DT>(zx_q));
+      }
     }
   }
 }
