@@ -406,7 +406,10 @@ namespace adasd {
 // distance at once; accepted positions that pass the open-interval filter are appended in position
 // order (rank = number of passing positions before it, from a ballot).
 // d: the lane's distance (lanes <= r, below kb), H: the draft entropy of the rejected position (lane r).
-__device__ inline void update_sequence_core(const UpdateArgs& a, int b, int lane, int r, int kb, float d, float H) {
+// Returns the status bits of the step (complete in the lane that finishes the sequence: lane r, or 63);
+// with or_status they are also OR-ed into status[b].
+__device__ inline uint32_t update_sequence_core(const UpdateArgs& a, int b, int lane, int r, int kb, float d, float H,
+                                                bool or_status = true) {
   const int nA = a.nA[b], nR = a.nR[b];
   double ent_sum = a.ent_sum[b];      // (asked for with the lengths: the last lane needs them at the very end)
   int ent_cnt = a.ent_cnt[b];
@@ -483,7 +486,7 @@ __device__ inline void update_sequence_core(const UpdateArgs& a, int b, int lane
       }
     }
   }
-  if (lane != fin) return;
+  if (lane != fin) return st;
   int nR_new = nR;
   if (r < kb) {
     if (isfinite(H)) {
@@ -500,7 +503,8 @@ __device__ inline void update_sequence_core(const UpdateArgs& a, int b, int lane
   a.nA[b] = nA_new;
   a.nR[b] = nR_new;
   a.T_G[b] = ent_cnt > 0 ? (float)(ent_sum / (double)ent_cnt) : 0.f;
-  if (a.status && st) a.status[b] |= st;
+  if (or_status && a.status && st) a.status[b] |= st;
+  return st;
 }
 
 // The update step right after the decisions of the same workgroup: distances and entropies as that
@@ -831,21 +835,36 @@ __device__ void decide_position_wide(const DecideArgs& a, const UpdateArgs& upd,
   if (!wsh.last || wave != 0) return;
 
   // ---- last workgroup of the sequence, one wavefront, one lane per position
+  // Every lane also asks for what the sampling plan and the update step need of ITS position (the
+  // normalisers, the drafted token, the draft entropy: all left by earlier kernels), so that nothing is
+  // loaded once the rejected position is known; its lane hands them over.
   int bits = 0;
   uint32_t pst = 0;
-  float dl = 0.f;
+  float dl = 0.f, Hl = 0.f;
+  double lse_p = 0.0, lse_q = 0.0;
+  int xl = -1;
   if (lane < K) {
-    const PosRecord* src = records + (size_t)b * K + lane;
+    const size_t ol = (size_t)b * K + lane;
+    const PosRecord* src = records + ol;
     bits = ld_agent(&src->bits);
     pst = (uint32_t)ld_agent(reinterpret_cast<const int*>(&src->status));
     dl = ld_agent(&src->d);
+    if (lane < kb) {
+      lse_p = ws.rows[2 * ol].lse2;
+      lse_q = ws.rows[2 * ol + 1].lse2;
+      if (a.base_test == 1) xl = a.draft_tokens[ol];
+      if (upd.B > 0) Hl = upd.H_q[ol];
+    }
   }
   const unsigned long long rejected = __ballot(lane < kb && !(bits & 1));
   const int r = rejected ? __ffsll((long long)rejected) - 1 : kb;
   uint32_t st_all = pst;
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) st_all |= __shfl_xor(st_all, off);
-  const int bad_r = __shfl(bits, r < 64 ? r : 63) & 2;
+  const int src_lane = r < 64 ? r : 63;
+  const int bad_r = __shfl(bits, src_lane) & 2;
+  const double lse_p_r = __shfl(lse_p, src_lane), lse_q_r = __shfl(lse_q, src_lane);
+  const int x_r = __shfl(xl, src_lane);
   if (lane == 0) {
     a.n_accept[b] = r;
     SamplePlan plan;
@@ -854,14 +873,13 @@ __device__ void decide_position_wide(const DecideArgs& a, const UpdateArgs& upd,
     if (r < kb) {
       plan.residual = 1;
       if (a.base_test == 1) {
-        const int x = a.draft_tokens[(size_t)b * K + r];
-        const bool x_ok = x >= 0 && x < a.map.V;
+        const bool x_ok = x_r >= 0 && x_r < a.map.V;
         plan.residual = x_ok ? 2 : 0;
-        plan.excluded = x_ok ? x : -1;
+        plan.excluded = x_ok ? x_r : -1;
       }
       plan.valid = !bad_r;
-      plan.lse2_p = ws.rows[2 * ((size_t)b * K + r)].lse2;
-      plan.lse2_q = ws.rows[2 * ((size_t)b * K + r) + 1].lse2;
+      plan.lse2_p = lse_p_r;
+      plan.lse2_q = lse_q_r;
     } else {
       plan.residual = 0;
       plan.valid = 1;
@@ -869,15 +887,17 @@ __device__ void decide_position_wide(const DecideArgs& a, const UpdateArgs& upd,
       plan.lse2_q = 0.0;
     }
     ws.plan[b] = plan;
-    a.status[b] = st_seq | st_all;
     __hip_atomic_store(&ws.ticket2[b * ticket_stride(a.map.B, kTicket2Len)], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+  uint32_t st_upd = 0;
   if (upd.B > 0) {
-    publish_barrier();           // the status word above is read and OR-ed by another lane below
-    float H = 0.f;
-    if (lane == r && r < kb) H = upd.H_q[(size_t)b * K + r];   // written by the statistics stage (an earlier kernel)
-    update_sequence_core(upd, b, lane, r, kb, dl, H);
+    // (a position with non-finite rows records nothing, whatever its entropy word holds by now)
+    const float H = (lane == r && r < kb && !(bits & 2)) ? Hl : NAN;
+    st_upd = update_sequence_core(upd, b, lane, r, kb, dl, H, false);
   }
+  // one store of the sequence's status word, the update step's bits included (they are complete in its last lane)
+  st_upd = __shfl(st_upd, src_lane);
+  if (lane == 0) a.status[b] = st_seq | st_all | st_upd;
 }
 
 }  // namespace adasd
