@@ -28,8 +28,110 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 STAGE_TRAFFIC_BYTES = 264.78e6
 # shapes: the headline workload is the one the metric is quoted on; "large" is a side measurement
 WORKLOADS = {"headline": (32, 8, 128256, 4),      # 4 sets x 139.5 MB of logits
-             "large": (128, 16, 152064, 2)}       # 2 sets x 1.28 GB
+             "large": (128, 16, 152064, 2),       # 2 sets x 1.28 GB
+             "closed_loop": (64, 16, 128256, 0)}  # fresh logits every round, generated on the device
 LIST_CAP = 8192
+
+
+def closed_loop(args, am, torch, B, k_max, V):
+    """Decode rounds from the initial state (T_G = 0, empty lists): per round, one adasd_draft_step call per
+    drafted token on the rows of the sequences still drafting (stop rule H(q) > T_G, drawn token x ~ q), then
+    adasd_verify on the ragged windows with the update step applied.  Fresh logits every round, generated on
+    the device with the recipe of the closed-loop configuration (std 3, spike 8, per-sequence mixing weight
+    on a +-0.02 random walk in [0.4, 0.99]); generation is outside every timed region."""
+    dev = "cuda"
+    g = torch.Generator(device=dev).manual_seed(0xADA5D + 4)
+    cap = 16384
+    ws = am.Workspace(B, k_max, V, torch.bfloat16)
+    state = am.State(B, cap)
+    out = am.binding.alloc_verify_result(B, k_max)
+    opts = am.Options(apply_update=1)
+    alpha = 0.5 + 0.4 * torch.rand(B, generator=g, device=dev)
+    H = torch.empty(B, dtype=torch.float32, device=dev)
+    stop = torch.empty(B, dtype=torch.uint8, device=dev)
+    dst = torch.empty(B, dtype=torch.int32, device=dev)
+    xT = torch.zeros(k_max, B, dtype=torch.int32, device=dev)
+    rounds = args.warmup + args.steps
+    wall = 0.0
+    kern_ms = [0.0] * 6
+    draft_calls = 0
+    positions = 0
+    accepted = 0
+    for r in range(rounds):
+        # ---- this round's logits (untimed)
+        walk = torch.where(torch.rand(B, generator=g, device=dev) < 0.5, -0.02, 0.02)
+        alpha = (alpha + walk).clamp(0.4, 0.99)
+        t = torch.randn(B, k_max + 1, V, generator=g, device=dev) * 3.0
+        idx = torch.randint(0, V, (B, k_max + 1, 1), generator=g, device=dev)
+        t.scatter_add_(2, idx, torch.full_like(idx, 8.0, dtype=torch.float32))
+        a3 = alpha.reshape(B, 1, 1)
+        d = (a3 * t[:, :k_max] + (1 - a3) * 3.0 * torch.randn(B, k_max, V, generator=g, device=dev)).to(torch.bfloat16)
+        t = t.to(torch.bfloat16)
+        active = torch.ones(B, dtype=torch.uint8, device=dev)
+        lens = torch.zeros(B, dtype=torch.int32, device=dev)
+        xT.zero_()
+        timed = r >= args.warmup
+        if timed:
+            am.profile_enable(k_max + 8)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        # ---- drafting: one call per drafted token while any sequence is still drafting
+        n_calls = 0
+        for step in range(k_max):
+            am.draft_step(d[:, step], ws, T_G=state.T_G, active=active, step=step, k_max=k_max, seed=7, round0=r,
+                          H_out=H, stop_out=stop, token_out=xT[step], status_out=dst)
+            n_calls += 1
+            lens += active.to(torch.int32)
+            active = active & (1 - stop)
+            if not bool(active.any()):          # (the host has to know when to stop calling the draft model)
+                break
+        x = xT.clamp(min=0).t().contiguous()
+        # ---- verification of the ragged windows, state updated by the same call
+        am.verify(t, d, x, ws, state=state, draft_len=lens, seed=7, round0=r, options=opts, out=out)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        if timed:
+            wall += t1 - t0
+            for c in range(6):
+                ms, _ = am.profile_read(c)
+                kern_ms[c] += ms
+            am.profile_disable()
+            draft_calls += n_calls
+            positions += int(lens.sum())
+            accepted += int(out.n_accept.sum())
+        if r % 50 == 0:
+            print(f"round {r}: mean window {float(lens.float().mean()):.2f}", file=sys.stderr, flush=True)
+    host = state.to_host()
+    steps = args.steps
+    kern_total = sum(kern_ms)
+    line = {
+        "metric": "verified positions/sec and achieved HBM GB/s (% peak) at B=32,k=8,V=128256 bf16",
+        "value": positions / wall,
+        "unit": "verified positions/s",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": wall / steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"closed loop B={B} V={V} k_max={k_max} bf16, {steps} decode rounds from the initial "
+                               f"state, fresh logits each round (device-generated), list capacity {cap}",
+                   "step": "adasd_draft_step per drafted token while any sequence drafts, then adasd_verify with "
+                           "options.apply_update on the ragged windows; wall time includes the host's per-call "
+                           "stop check and the small tensor ops of the loop"},
+        "roofline": None,
+        "cpu_baseline": None,
+        "closed_loop": {
+            "mean_window_k_b": positions / (steps * B),
+            "mean_accepted_length": accepted / (steps * B),
+            "draft_calls_per_round": draft_calls / steps,
+            "kernel_us_per_round": {"row_stats": kern_ms[0] / steps * 1e3, "jsd": kern_ms[1] / steps * 1e3,
+                                    "decide": kern_ms[2] / steps * 1e3, "sample": kern_ms[3] / steps * 1e3,
+                                    "draft_step_all_calls": kern_ms[5] / steps * 1e3},
+            "draft_step_kernel_us_per_call": kern_ms[5] / max(draft_calls, 1) * 1e3,
+            "positions_per_s_kernel_time_only": positions / (kern_total * 1e-3) if kern_total > 0 else None,
+            "list_lengths_at_end": {"accepted_mean": float(host["nA"].mean()), "rejected_mean": float(host["nR"].mean())},
+            "T_G_mean_at_end": float(host["T_G"].mean()),
+        },
+    }
+    print(json.dumps(line))
 
 
 def main():
@@ -39,8 +141,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="headline",
-                    help="headline: B=32 k=8 V=128256 (the metric's workload); large: B=128 k=16 V=152064 "
-                         "(side measurement, no CPU baseline, no counter-derived traffic figure)")
+                    help="headline: B=32 k=8 V=128256 (the metric's workload); large: B=128 k=16 V=152064; "
+                         "closed_loop: B=64 k_max=16 V=128256, a step is one decode round (drafting calls until "
+                         "every sequence has stopped, then verify + update) from the initial state "
+                         "(side measurements, no CPU baseline, no counter-derived traffic figure)")
     ap.add_argument("--sets", type=int, default=0, help="rotating input sets (0: the workload's default)")
     ap.add_argument("--stats-path", type=int, default=0, help="0 library default, 1 two-kernel path, 2 single-read kernel")
     ap.add_argument("--separate-update", action="store_true",
@@ -78,6 +182,8 @@ def main():
     am.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.workload == "closed_loop":
+        return closed_loop(args, am, torch, B, K, V)
 
     # ---- seeded synthetic inputs, resident in HBM before any timing
     sets = []

@@ -59,6 +59,7 @@ constexpr size_t kRegionBytes[] = {
     (size_t)kMaxSampleSplit * sizeof(Top2),               // part3
     sizeof(PosRecord),                                    // pos_rec
     sizeof(float2),                                       // tok
+    sizeof(int32_t),                                      // slots
 };
 constexpr size_t per_position_bytes() {
   size_t t = 0;
@@ -68,11 +69,11 @@ constexpr size_t per_position_bytes() {
 }  // namespace
 
 size_t workspace_bytes_for(size_t positions) {
-  return kHeaderBytes + (positions + 1) * per_position_bytes() + 10 * 256;
+  return kHeaderBytes + (positions + 1) * per_position_bytes() + 11 * 256;
 }
 
 size_t workspace_layout(size_t ws_bytes, Workspace* ws, void* base) {
-  const size_t slack = kHeaderBytes + 10 * 256;
+  const size_t slack = kHeaderBytes + 11 * 256;
   if (ws_bytes <= slack) return 0;
   const size_t cap = (ws_bytes - slack) / per_position_bytes();
   if (ws && cap > 0) {
@@ -97,6 +98,7 @@ size_t workspace_layout(size_t ws_bytes, Workspace* ws, void* base) {
     ws->part3 = reinterpret_cast<Top2*>(take(cap * kRegionBytes[7]));
     ws->pos_rec = reinterpret_cast<PosRecord*>(take(cap * kRegionBytes[8]));
     ws->tok = reinterpret_cast<float2*>(take(cap * kRegionBytes[9]));
+    ws->slots = reinterpret_cast<int32_t*>(take(cap * kRegionBytes[10]));
     ws->bytes = off;
   }
   return cap;
@@ -419,15 +421,20 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   } else if (K > 0) {
     const int rows = B * K * 2;
     const int S = pick_split(rows, V, (int)a->dt);
+    RowMap smap = map;
     {
       Scope sc(0, st);
-      if (launch_rowstats(map, (int)a->dt, rows, S, ws, st) != hipSuccess) return ADASD_ERR_HIP;
+      if (a->draft_len) {        // ragged windows: the positions that have work, packed
+        if (launch_pack_slots(a->draft_len, B, K, ws.slots, st) != hipSuccess) return ADASD_ERR_HIP;
+        smap.slots = ws.slots;
+      }
+      if (launch_rowstats(smap, (int)a->dt, rows, S, ws, st) != hipSuccess) return ADASD_ERR_HIP;
     }
     {
       Scope sc(1, st);
       vout.tokens = a->draft_tokens;
       vout.tok = a->draft_tokens ? ws.tok : nullptr;
-      if (launch_jsd(map, (int)a->dt, S, S, ws, vout, st) != hipSuccess) return ADASD_ERR_HIP;
+      if (launch_jsd(smap, (int)a->dt, S, S, ws, vout, st) != hipSuccess) return ADASD_ERR_HIP;
     }
     d.jsd_split = S;
     d.tok = vout.tok;

@@ -27,6 +27,8 @@ struct RowMap {
   int64_t seq_stride[2], pos_stride[2];  // elements
   const int32_t* draft_len;              // [B] or null
   const uint8_t* active;                 // [B] or null (draft-entropy mode)
+  const int32_t* slots;                  // [B*K] or null: the candidate positions inside their windows, packed
+                                         // (window position first, sequence second), -1 behind them
   int32_t K;                             // k_max; 0 selects draft-entropy mode (one row per sequence)
   int32_t B, V;
 };
@@ -44,7 +46,8 @@ struct Workspace {
   uint64_t* fused_slots; // [positions][kMaxFusedSplit][kSlotWords] self-validating hand-off words, zero between calls
   uint64_t* fused_norm;  // [positions][kSlotWords] folded triples of both rows, published by the position's leader
   PosRecord* pos_rec; // [positions] outcomes of the positions (long-history decision kernel)
-  float2* tok;        // [positions] logits of the drafted tokens gathered from the column shards
+  float2* tok;        // [positions] logits of the drafted tokens (looked up by the JS kernel or by the column shards)
+  int32_t* slots;     // [positions] packed list of the positions inside their windows (ragged calls)
   size_t bytes;
 };
 
@@ -107,6 +110,10 @@ inline void launch_kernel(Kernel kernel, dim3 grid, dim3 block, hipStream_t st, 
 }
 
 int pick_split(int rows, int V, int dt);
+
+// Ragged windows: the positions i < draft_len[b] of all sequences, packed into slots[0 .. n) in the order
+// (window position, sequence), -1 in the remaining slots up to B*K (one small kernel).
+hipError_t launch_pack_slots(const int32_t* draft_len, int B, int K, int32_t* slots, hipStream_t st);
 
 // plain streaming read (diagnostics): one word per workgroup goes to `sink`
 size_t stream_read_groups(size_t bytes);

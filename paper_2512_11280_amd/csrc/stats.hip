@@ -33,7 +33,13 @@ __global__ void __launch_bounds__(kBlock, 8)   // 64 registers: eight wavefronts
 k_rowstats(RowMap map, int S, Workspace ws) {
   warm_kernargs<sizeof(RowMap) + sizeof(int) + sizeof(Workspace)>();
   constexpr int EPV = Elem<DT>::per_vec;
-  const int rho = blockIdx.y, s = blockIdx.x, tid = threadIdx.x;
+  const int s = blockIdx.x, tid = threadIdx.x;
+  int rho = blockIdx.y;
+  if (map.K > 0) {
+    const int p = position_of_slot(map, blockIdx.y >> 1);
+    if (p < 0) return;
+    rho = 2 * p + (blockIdx.y & 1);
+  }
   const RowRef r = locate_row<DT>(map, rho);
   if (!r.active) return;
   const int V = map.V;
@@ -120,9 +126,10 @@ __global__ void __launch_bounds__(kBlock)
 k_jsd(RowMap map, int S, int S_fold, Workspace ws, VerifyOut vout) {
   warm_kernargs<sizeof(RowMap) + 2 * sizeof(int) + sizeof(Workspace) + sizeof(VerifyOut)>();
   constexpr int EPV = Elem<DT>::per_vec;
-  const int pos = blockIdx.y, s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int pos = position_of_slot(map, blockIdx.y), s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   __shared__ RowResult sh_row[2];
   __shared__ float sha[kWaves];
+  if (pos < 0) return;
   const RowRef rp = locate_row<DT>(map, 2 * pos), rq = locate_row<DT>(map, 2 * pos + 1);
   if (!rp.active) return;
   const int V = map.V;
@@ -220,6 +227,52 @@ k_jsd(RowMap map, int S, int S_fold, Workspace ws, VerifyOut vout) {
 }
 
 }  // namespace
+
+namespace {
+
+// One workgroup (as many wavefronts as 64 sequences each, at most 16): for every window position i in turn,
+// the sequences whose window holds it, ranked by a ballot per wavefront and the wavefronts' counts.
+__global__ void __launch_bounds__(1024) k_pack_slots(const int32_t* __restrict__ draft_len, int B, int K,
+                                                     int32_t* __restrict__ slots) {
+  __shared__ int sh_cnt[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nt = blockDim.x, nw = nt >> 6;
+  int base = 0;                                   // (every thread keeps the same count)
+  for (int b0 = 0; b0 < B; b0 += nt) {            // (more sequences than threads: their chunks one after the other)
+    const int b = b0 + tid;
+    const int kb = b < B ? min(max(draft_len[b], 0), K) : 0;
+    for (int i = 0; i < K; ++i) {
+      const bool in = i < kb;
+      const unsigned long long m = __ballot(in);
+      if (nw > 1) {
+        __syncthreads();                          // (the counts of the previous turn have been read)
+        if (lane == 0) sh_cnt[wave] = __popcll(m);
+        __syncthreads();
+      }
+      int before = base, total = 0;
+      if (nw > 1) {
+        for (int w = 0; w < nw; ++w) {
+          before += w < wave ? sh_cnt[w] : 0;
+          total += sh_cnt[w];
+        }
+      } else {
+        total = __popcll(m);
+      }
+      if (in) slots[before + __popcll(m & ((1ull << lane) - 1ull))] = b * K + i;
+      base += total;
+    }
+  }
+  for (int m = base + tid; m < B * K; m += nt) slots[m] = -1;
+}
+
+}  // namespace
+
+hipError_t launch_pack_slots(const int32_t* draft_len, int B, int K, int32_t* slots, hipStream_t st) {
+  if (B <= 0 || K <= 0) return hipSuccess;
+  int threads = (B + 63) / 64 * 64;
+  if (threads > 1024) threads = 1024;
+  launch_kernel(k_pack_slots, dim3(1), dim3(threads), st, draft_len, B, K, slots);
+  return hipGetLastError();
+}
 
 int pick_split(int rows, int V, int dt) {
   const int epv = dt == ADASD_BF16 ? 8 : 4;

@@ -20,7 +20,7 @@ __device__ __forceinline__ RowRef locate_row(const RowMap& map, int rho) {
     r.b = pos / map.K;
     r.i = pos - r.b * map.K;
     int kb = map.K;
-    if (map.draft_len) kb = min(max(map.draft_len[r.b], 0), map.K);
+    if (map.draft_len && !map.slots) kb = min(max(map.draft_len[r.b], 0), map.K);   // (a packed slot list only names positions inside their windows)
     r.active = r.i < kb;
   } else {
     r.which = 0;
@@ -31,6 +31,20 @@ __device__ __forceinline__ RowRef locate_row(const RowMap& map, int rho) {
   int64_t off = (int64_t)r.b * map.seq_stride[r.which] + (int64_t)r.i * map.pos_stride[r.which];
   r.ptr = map.base[r.which] + off * Elem<DT>::bytes;
   return r;
+}
+
+// The candidate position that the m-th position slot of a launch works on, or -1 for none.  With ragged
+// windows (draft_len given) the positions past a window's end have no work and their workgroups leave at
+// once; in storage order they recur with period k_max, and the placement of consecutive workgroups on
+// consecutive compute units turns that period into compute units without work (measured: the JS kernel
+// took as long for half-length windows as for full ones).  So the slots either follow a packed list of
+// the positions that have work (map.slots), or, without one, run over the sequences first and the
+// window position second, which at least moves the empty positions to the end of the dispatch order.
+__device__ __forceinline__ int position_of_slot(const RowMap& map, int m) {
+  if (!map.draft_len) return m;
+  if (map.slots) return map.slots[m];
+  const int i = m / map.B, b = m - i * map.B;
+  return b * map.K + i;
 }
 
 __device__ __forceinline__ bool aligned16(const void* p) {

@@ -148,6 +148,35 @@ def test_ragged_lengths_sequence_ids_and_rounds(am, wl, oracle, path):
     assert out.n_accept[0].item() == 0 and out.H_q[0].abs().sum().item() == 0
 
 
+@pytest.mark.parametrize("B,K,V", [(70, 9, 1032), (130, 3, 520), (1100, 2, 264), (64, 16, 2056), (3, 64, 520)])
+def test_ragged_windows_of_many_sequences(am, wl, oracle, B, K, V):
+    """Ragged windows go through a packed list of the positions that have work: one wavefront of
+    sequences, several wavefronts, more sequences than one workgroup has threads, the longest window;
+    lengths from 0 to k_max and beyond (clamped and flagged)."""
+    batch = wl.config_batched(B=B, k=K, V=V, seed=B * 1000 + K, cap=64)
+    rng = np.random.default_rng(B + K)
+    lens = rng.integers(0, K + 1, B)
+    lens[0] = 0
+    lens[-1] = K
+    if B > 2:
+        lens[1] = K + 3                     # out of range: clamped to k_max, flagged
+    batch.draft_len = torch.tensor(np.minimum(lens, K), dtype=torch.int32)
+    ref = G.run_oracle(oracle, batch)
+    batch.draft_len = torch.tensor(lens, dtype=torch.int32)
+    out, _, _ = G.run_gpu(am, batch)
+    st = out.status.cpu().numpy()
+    if B > 2:
+        assert st[1] & am.binding.ST_BAD_LENGTH
+        st[1] &= ~am.binding.ST_BAD_LENGTH
+        out.status = torch.tensor(st, device="cuda")
+    rep = G.compare_verify(out, ref, info_bits=16 | 8)
+    _report(f"ragged B={B} K={K}", rep)
+    # positions past a window's end hold the filler, never a stale value
+    H = out.H_q.cpu().numpy()
+    for b in range(B):
+        assert (H[b, min(lens[b], K):] == 0).all()
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("V", [8, 100, 1001, 4096, 20011])
 def test_small_and_ragged_vocabularies(am, wl, oracle, dtype, V, path):
