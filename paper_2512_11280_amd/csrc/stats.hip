@@ -126,7 +126,10 @@ __global__ void __launch_bounds__(kBlock)
 k_jsd(RowMap map, int S, int S_fold, Workspace ws, VerifyOut vout) {
   warm_kernargs<sizeof(RowMap) + 2 * sizeof(int) + sizeof(Workspace) + sizeof(VerifyOut)>();
   constexpr int EPV = Elem<DT>::per_vec;
-  const int pos = position_of_slot(map, blockIdx.y), s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // Full windows: the positions in reverse storage order.  The first kernel went through them forwards, so
+  // what it read last (and what the XCDs' L2 caches may still hold) is asked for first (-0.6 us measured).
+  const int slot = map.draft_len ? (int)blockIdx.y : (int)(gridDim.y - 1 - blockIdx.y);
+  const int pos = position_of_slot(map, slot), s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   __shared__ RowResult sh_row[2];
   __shared__ float sha[kWaves];
   if (pos < 0) return;
