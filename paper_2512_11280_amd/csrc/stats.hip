@@ -52,17 +52,22 @@ k_rowstats(RowMap map, int S, Workspace ws) {
   Lse extra = lse_empty();
   if (aligned16(r.ptr)) {
     const int nv = V / EPV;
-    const int chunk = (nv + S - 1) / S, v0 = min(s * chunk, nv), v1 = min(v0 + chunk, nv);
+    const int chunk = slice_vectors(nv, S), v0 = min(s * chunk, nv), v1 = min(v0 + chunk, nv);
     const uint4* vec = reinterpret_cast<const uint4*>(r.ptr);
     const uint4 neutral = neutral_vec<DT>();
     for (int base = v0; base < v1; base += kRowBatch * kBlock) {
       uint4 v[kRowBatch];
+      if (base + kRowBatch * kBlock <= v1) {          // (uniform) a whole batch: every lane has its vectors
 #pragma unroll
-      for (int j = 0; j < kRowBatch; ++j) {
-        const int idx = base + tid + j * kBlock;
-        const bool in = idx < v1;
-        const uint4 x = vec[in ? idx : v1 - 1];
-        v[j] = make_uint4(in ? x.x : neutral.x, in ? x.y : neutral.y, in ? x.z : neutral.z, in ? x.w : neutral.w);
+        for (int j = 0; j < kRowBatch; ++j) v[j] = vec[base + tid + j * kBlock];
+      } else {
+#pragma unroll
+        for (int j = 0; j < kRowBatch; ++j) {
+          const int idx = base + tid + j * kBlock;
+          const bool in = idx < v1;
+          const uint4 x = vec[in ? idx : v1 - 1];
+          v[j] = make_uint4(in ? x.x : neutral.x, in ? x.y : neutral.y, in ? x.z : neutral.z, in ? x.w : neutral.w);
+        }
       }
       const float mb = wave_max_f(vecs_max<DT, kRowBatch>(v));
       if (mb > M) {                       // wave-uniform
@@ -138,13 +143,21 @@ k_jsd(RowMap map, int S, int S_fold, Workspace ws, VerifyOut vout) {
   const int V = map.V;
   const bool vec_path = aligned16(rp.ptr) && aligned16(rq.ptr);
   const int nv = V / EPV;
-  const int chunk = (nv + S - 1) / S, v0 = min(s * chunk, nv), v1 = min(v0 + chunk, nv);
+  const int chunk = slice_vectors(nv, S), v0 = min(s * chunk, nv), v1 = min(v0 + chunk, nv);
   const uint4* vp = reinterpret_cast<const uint4*>(rp.ptr);
   const uint4* vq = reinterpret_cast<const uint4*>(rq.ptr);
   const uint4 neutral = neutral_vec<DT>();
   uint4 xp[kJsdBatch], xq[kJsdBatch];
   // one batch of vector pairs: all loads in flight at once; a pair masked in both rows contributes 0
   auto load_batch = [&](int base) {
+    if (base + kJsdBatch * kBlock <= v1) {          // (uniform) a whole batch: every lane has its vectors
+#pragma unroll
+      for (int j = 0; j < kJsdBatch; ++j) {
+        xp[j] = vp[base + tid + j * kBlock];
+        xq[j] = vq[base + tid + j * kBlock];
+      }
+      return;
+    }
 #pragma unroll
     for (int j = 0; j < kJsdBatch; ++j) {
       const int idx = base + tid + j * kBlock;

@@ -47,6 +47,15 @@ __device__ __forceinline__ int position_of_slot(const RowMap& map, int m) {
   return b * map.K + i;
 }
 
+// Vectors per slice of a row of nv vectors cut into S slices: a multiple of the workgroup size where the
+// last slice then still has work, so that all slices but the last consist of whole batches (no lane is
+// ever past the end there, and the loads need neither clamping nor masking).
+__device__ __forceinline__ int slice_vectors(int nv, int S) {
+  const int chunk = (nv + S - 1) / S;
+  const int rounded = (chunk + kBlock - 1) / kBlock * kBlock;
+  return (int64_t)rounded * (S - 1) < nv ? rounded : chunk;
+}
+
 __device__ __forceinline__ bool aligned16(const void* p) {
   return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
 }
