@@ -46,7 +46,10 @@ k_rowstats(RowMap map, int S, Workspace ws) {
   // Vector path: batches of kRowBatch vectors per thread are loaded up front (all loads of a batch in
   // flight at once), the batch's largest finite logit becomes the wavefront's reference if it exceeds
   // the current one, and every element then costs one exp and a handful of multiply-adds: no
-  // per-element rescaling, no divergent branch.  Elements outside whole vectors (unaligned rows, the
+  // per-element rescaling, no divergent branch.  (Working through a batch vector by vector as the loads
+  // come back, with a reference from the first of them, measured 7 us slower on 512 rows of 128256
+  // logits: a wavefront that waits for its whole batch and then runs through it leaves early, and its
+  // successor's loads are on their way sooner.)  Elements outside whole vectors (unaligned rows, the
   // last V mod EPV logits) take the one-at-a-time online form in `extra`.
   float M = kNegHuge, s0 = 0.f, s1 = 0.f, u0 = 0.f, u1 = 0.f;
   Lse extra = lse_empty();
