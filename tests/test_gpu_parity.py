@@ -148,7 +148,8 @@ def test_ragged_lengths_sequence_ids_and_rounds(am, wl, oracle, path):
     assert out.n_accept[0].item() == 0 and out.H_q[0].abs().sum().item() == 0
 
 
-@pytest.mark.parametrize("B,K,V", [(70, 9, 1032), (130, 3, 520), (1100, 2, 264), (64, 16, 2056), (3, 64, 520)])
+@pytest.mark.parametrize("B,K,V", [(70, 9, 1032), (130, 3, 520), (1100, 2, 264), (64, 16, 2056), (3, 64, 520),
+                                   (32767, 1, 16), (16383, 2, 24)])
 def test_ragged_windows_of_many_sequences(am, wl, oracle, B, K, V):
     """Ragged windows go through a packed list of the positions that have work: one wavefront of
     sequences, several wavefronts, more sequences than one workgroup has threads, the longest window;
