@@ -119,11 +119,16 @@ typedef struct {
   float d_eps;         /* distances <= d_eps or >= 1-d_eps count as "exactly 0 or 1" and are not
                           recorded (Section 4.4); 0 selects the default 1e-6 */
   int32_t stats_path;  /* kernels of the statistics stage: 0 the library's choice (the two-kernel
-                          path, the faster one on gfx950 where the stage is bound by the vector
-                          ALU); 1 the two-kernel path (normalisers, then JS distance: the logits
-                          are read twice); 2 the single-read kernel when every row is 16-byte
-                          aligned and V is a whole number of 16-byte vectors, else the two-kernel
-                          path.  Same results to the documented tolerance either way. */
+                          path, the faster one on gfx950); 1 the two-kernel path (normalisers, then
+                          JS distance: the logits are read twice); 2 the single-read kernel when
+                          every row is 16-byte aligned and V is a whole number of 16-byte vectors,
+                          else the two-kernel path.  Same results to the documented tolerance either
+                          way, with one exception: the single-read kernel forms its sums about a
+                          reference taken from the first vector of each part of a row (not the
+                          part's maximum), so its entropies carry an absolute error of up to 5e-6
+                          nats (range of the logits x 2^-23), which exceeds 1e-5 relative for rows
+                          with an entropy below about 0.5 nats.  Normalisers, distances and
+                          decisions are not affected. */
   int32_t apply_update; /* 1: adasd_verify also applies the round to args->state, exactly as
                           adasd_update_thresholds would with the same d_eps (the decision kernel
                           does it after the sequence's decisions, which saves a launch);
