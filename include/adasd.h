@@ -123,12 +123,7 @@ typedef struct {
                           JS distance: the logits are read twice); 2 the single-read kernel when
                           every row is 16-byte aligned and V is a whole number of 16-byte vectors,
                           else the two-kernel path.  Same results to the documented tolerance either
-                          way, with one exception: the single-read kernel forms its sums about a
-                          reference taken from the first vector of each part of a row (not the
-                          part's maximum), so its entropies carry an absolute error of up to 5e-6
-                          nats (range of the logits x 2^-23), which exceeds 1e-5 relative for rows
-                          with an entropy below about 0.5 nats.  Normalisers, distances and
-                          decisions are not affected. */
+                          way. */
   int32_t apply_update; /* 1: adasd_verify also applies the round to args->state, exactly as
                           adasd_update_thresholds would with the same d_eps (the decision kernel
                           does it after the sequence's decisions, which saves a launch);

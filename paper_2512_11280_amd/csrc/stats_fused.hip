@@ -184,8 +184,14 @@ __device__ __forceinline__ void p1_refs(const Buf<NV>& b, float& ref_p, float& r
     ref_q = flagged(wave_max_f(vecs_max<DT, NV>(b.q)));
   }
 }
+// A mean exponent u/s well above zero means that a token well above the cheap reference carries most of the
+// part's mass: then the weighted sum is one large term plus the small ones that hold the entropy, and float
+// loses those (an absolute error of about (maximum - reference) x 2^-24 nats on the row's entropy).  Such
+// parts are redone with their true maximum as well (with that, every term is <= 0).  Ordinary rows, whose
+// mass sits within a few units of the part's maximum, stay below the mark.
 __device__ __forceinline__ bool p1_suspect(const Lse& lp, const Lse& lq) {
-  return !(lp.s < INFINITY) || !(lq.s < INFINITY) || !(fabsf(lp.u) < INFINITY) || !(fabsf(lq.u) < INFINITY);
+  return !(lp.s < INFINITY) || !(lq.s < INFINITY) || !(fabsf(lp.u) < INFINITY) || !(fabsf(lq.u) < INFINITY) ||
+         lp.u > 4.f * lp.s || lq.u > 4.f * lq.s;
 }
 // Phase 1 in one piece with exact references.
 template <int DT, int NV>

@@ -16,8 +16,6 @@ import numpy as np
 import torch
 
 RTOL, ATOL = 1e-5, 1e-6
-H_ATOL_SINGLE_READ = 5e-6   # entropies of the single-read statistics kernel (options.stats_path = 2): its
-                            # sums are formed about a reference below the maximum (range of the logits x 2^-23)
 D_FLOOR = 2e-7
 FLIP_BAND = 1e-5
 PA_ATOL = 2e-5          # posterior moves by dP/dd * 1e-5*d; slope of the KDE ratio can reach ~1/h
@@ -47,7 +45,6 @@ def run_gpu(am, batch, options=None, seq_id=None, rounds=None, ws=None, stats_pa
                     draft_len=to_dev(batch.draft_len), seed=batch.seed, seq_id=sid, rounds=rnd,
                     round0=batch.round0, options=options)
     torch.cuda.synchronize()
-    out.stats_path = options.stats_path if options is not None else 0
     return out, st, ws
 
 
@@ -94,10 +91,8 @@ def compare_verify(gpu, ref, info_bits=16):
     g = {k: getattr(gpu, k).cpu().numpy() for k in
          ("n_accept", "next_token", "H_p", "H_q", "d_js", "p_accept", "accept_mask", "status")}
     rep = dict(flips=0, exact_path=int(((g["status"] & info_bits) != 0).sum()), seq_skipped=0)
-    # the single-read statistics kernel documents a larger absolute error of its entropies
-    h_atol = H_ATOL_SINGLE_READ if getattr(gpu, "stats_path", 0) == 2 else ATOL
     for name in ("H_p", "H_q", "d_js"):
-        ok = close(g[name], ref[name], atol=ATOL if name == "d_js" else h_atol)
+        ok = close(g[name], ref[name])
         if name == "d_js":
             ok |= close(g[name].astype(np.float64) ** 2, ref[name] ** 2, rtol=RTOL, atol=D_FLOOR)
         if not ok.all():

@@ -151,8 +151,8 @@ def test_ragged_lengths_sequence_ids_and_rounds(am, wl, oracle, path):
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_entropy_of_rows_with_nearly_all_mass_on_one_token(am, wl, oracle, dtype, path):
     """Entropies far below 1 nat: the heaviest token sits late in the row, so a reference taken from the
-    start of the row is far below the maximum.  The default kernels meet 1e-5 |H| + 1e-6; the
-    single-read kernel has a documented absolute floor of 5e-6 nats (gpu_util applies it)."""
+    start of the row is far below the maximum (the single-read kernel starts from such a reference and
+    has to notice; a randomised sweep once found 2e-6 nats of error on a row with H = 0.067)."""
     batch = wl.config_batched(B=3, k=4, V=4104, seed=77, dtype=dtype)
     g = torch.Generator().manual_seed(5)
     for b in range(3):
