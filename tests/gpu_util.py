@@ -102,12 +102,34 @@ def compare_verify(gpu, ref, info_bits=16):
     # The posterior is a steep function of the distance where the kernel bandwidth is small, so an
     # admissible error of the distance can move it by more than PA_ATOL.  Where the direct comparison
     # fails, the posterior must still agree with the oracle's evaluated at the distance the GPU found.
+    # With appends inside the loop an earlier position's distance is part of the list.  The divergence has an
+    # absolute floor (D_FLOOR), so a distance below about 1e-3 is not resolved by the kernels: it can fall on
+    # the other side of the open-interval filter than the oracle's, or join the list with another value.
+    # Then the sequence's later posteriors belong to another list; like an acceptance flip this is counted
+    # and the rest of the sequence is not compared.
+    d_eps = ref.get("d_eps", 1e-6)
+    dg, dr = g["d_js"].astype(np.float64), np.asarray(ref["d_js"], dtype=np.float64)
+    with np.errstate(invalid="ignore"):
+        member_flip = ((dg > d_eps) & (dg < 1 - d_eps)) != ((dr > d_eps) & (dr < 1 - d_eps))
+        unresolved = member_flip | ((dr > d_eps) & (dr * dr <= 5 * D_FLOOR)) | \
+            ((dr < 1 - d_eps) & (1 - dr * dr <= 5 * D_FLOOR))
+    member_seq = np.zeros(g["n_accept"].shape[0], dtype=bool)
     okp = close(g["p_accept"], ref["p_accept"], rtol=0.0, atol=PA_ATOL)
     for b, i in np.argwhere(~okp):
+        if member_seq[b]:
+            continue
         at_gpu_d = ref["posterior_at"](b, i, g["d_js"][b, i])
-        assert abs(g["p_accept"][b, i] - at_gpu_d) <= PA_ATOL, \
-            f"p_accept mismatch at {(b, i)}: gpu {g['p_accept'][b, i]!r}, oracle at the same distance " \
-            f"{at_gpu_d!r}, oracle at its own distance {ref['p_accept'][b, i]!r}"
+        if abs(g["p_accept"][b, i] - at_gpu_d) <= PA_ATOL:
+            continue
+        if unresolved[b, :i].any():
+            member_seq[b] = True
+            continue
+        raise AssertionError(
+            f"p_accept mismatch at {(b, i)}: gpu {g['p_accept'][b, i]!r}, oracle at the same distance "
+            f"{at_gpu_d!r}, oracle at its own distance {ref['p_accept'][b, i]!r}")
+    rep["member_flips"] = int(member_seq.sum())
+    rep["unresolved"] = int(np.nansum(unresolved))      # distances the kernels cannot tell from 0 or 1: the lists
+                                                        # they go into may differ from the oracle's
     rep["max_rel_H"] = float(np.nanmax(np.abs(g["H_q"] - ref["H_q"]) / np.maximum(np.abs(ref["H_q"]), 1e-30),
                                        initial=0.0))
     rep["max_rel_d"] = float(np.nanmax(np.abs(g["d_js"] - ref["d_js"]) / np.maximum(np.abs(ref["d_js"]), 1e-30),
@@ -115,9 +137,9 @@ def compare_verify(gpu, ref, info_bits=16):
 
     B = g["n_accept"].shape[0]
     gm, rm = g["accept_mask"], ref["accept_mask"]
-    flipped_seq = np.zeros(B, dtype=bool)
+    flipped_seq = member_seq.copy()
     for bit, margin in ((1, ref["base_margin"]), (2, ref["relaxed_margin"])):
-        diff = (gm & bit) != (rm & bit)
+        diff = ((gm & bit) != (rm & bit)) & ~member_seq[:, None]
         if diff.any():
             assert (np.abs(margin[diff]) <= FLIP_BAND).all(), \
                 f"acceptance bit {bit} differs outside the 1e-5 band: margins {margin[diff]}"

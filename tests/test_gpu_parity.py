@@ -31,9 +31,9 @@ def path(request):
 
 
 def _report(name, rep):
-    print(f"[parity] {name}: flips={rep['flips']} skipped_seq={rep['seq_skipped']} "
-          f"exact_path={rep['exact_path']} max_rel_H={rep['max_rel_H']:.2e} max_rel_d={rep['max_rel_d']:.2e}",
-          flush=True)
+    print(f"[parity] {name}: flips={rep['flips']} member_flips={rep['member_flips']} unresolved={rep['unresolved']} "
+          f"skipped_seq={rep['seq_skipped']} exact_path={rep['exact_path']} max_rel_H={rep['max_rel_H']:.2e} "
+          f"max_rel_d={rep['max_rel_d']:.2e}", flush=True)
 
 
 # ------------------------------------------------------------------------------- the five shapes
@@ -339,7 +339,7 @@ def test_literal_variant_with_the_update_in_the_same_call(am, wl, oracle):
     host = {k: np.array(v, copy=True) for k, v in batch.state.items()}
     oracle.update(host, ref["n_accept"], batch.draft_len.numpy(), ref["H_q"], ref["d_js"], batch.k, d_eps=1e-6)
     got = st.to_host()
-    if rep["flips"] == 0:
+    if rep["flips"] == 0 and rep["unresolved"] == 0:
         for k in ("nA", "nR", "ent_cnt"):
             assert np.array_equal(got[k], host[k]), k
 
@@ -1138,7 +1138,7 @@ def test_closed_loop_rounds_against_oracle(am, wl, oracle, mode):
         am.update_thresholds(dev, W, out.n_accept, out.H_q, out.d_js, draft_len=dl_gpu)
         got_before = dev.to_host()
         oracle.update(host, ref["n_accept"], dl_ref, ref["H_q"], ref["d_js"], W)
-        if rep["flips"] == 0:
+        if rep["flips"] == 0 and rep["unresolved"] == 0:
             assert np.array_equal(got_before["nA"], host["nA"]) and np.array_equal(got_before["nR"], host["nR"])
             assert np.allclose(got_before["T_G"], host["T_G"], rtol=1e-5)
             for b in range(B):
