@@ -61,15 +61,16 @@ def run_oracle(oracle, batch, options=None, seq_id=None, rounds=None):
                         LA=s["LA"], LR=s["LR"], nA=s["nA"], nR=s["nR"], seed=batch.seed,
                         seq_id=seq_id, rounds=rounds, round0=batch.round0, **kw)
 
-    def posterior_at(b, i, d):
+    def posterior_at(b, i, d, earlier=None):
         """The oracle's posterior of sequence b, position i, at a given distance (for the p_accept
-        check).  With appends inside the loop the list is the state's followed by the oracle's own
-        distances of the earlier positions that pass the filter and fit the capacity."""
+        check).  With appends inside the loop the list is the state's followed by the distances of the
+        earlier positions that pass the filter and fit the capacity: the oracle's own, or `earlier`
+        (the ones another implementation found, within their tolerance)."""
         la = list(s["LA"][b, :int(s["nA"][b])])
         if kw.get("list_update", 0):
             eps, cap = kw["d_eps"], s["LA"].shape[1]
             for j in range(i):
-                dj = ref["d_js"][b, j]
+                dj = ref["d_js"][b, j] if earlier is None else earlier[j]
                 if eps < dj < 1.0 - eps and len(la) < cap:
                     la.append(np.float32(dj))
         return oracle.posterior(float(d), np.float32(la), s["LR"][b, :int(s["nR"][b])],
@@ -103,10 +104,11 @@ def compare_verify(gpu, ref, info_bits=16):
     # admissible error of the distance can move it by more than PA_ATOL.  Where the direct comparison
     # fails, the posterior must still agree with the oracle's evaluated at the distance the GPU found.
     # With appends inside the loop an earlier position's distance is part of the list.  The divergence has an
-    # absolute floor (D_FLOOR), so a distance below about 1e-3 is not resolved by the kernels: it can fall on
-    # the other side of the open-interval filter than the oracle's, or join the list with another value.
-    # Then the sequence's later posteriors belong to another list; like an acceptance flip this is counted
-    # and the rest of the sequence is not compared.
+    # absolute floor (D_FLOOR), so a small distance carries a relative error above 1e-5 (below about 1e-3 it
+    # is not resolved at all): it can fall on the other side of the open-interval filter than the oracle's,
+    # or join the list with a slightly different value.  Then the sequence's later posteriors belong to
+    # another list: they must agree with the oracle's posterior on THAT list; like an acceptance flip this is
+    # counted and the rest of the sequence is not compared.
     d_eps = ref.get("d_eps", 1e-6)
     dg, dr = g["d_js"].astype(np.float64), np.asarray(ref["d_js"], dtype=np.float64)
     with np.errstate(invalid="ignore"):
@@ -121,7 +123,10 @@ def compare_verify(gpu, ref, info_bits=16):
         at_gpu_d = ref["posterior_at"](b, i, g["d_js"][b, i])
         if abs(g["p_accept"][b, i] - at_gpu_d) <= PA_ATOL:
             continue
-        if unresolved[b, :i].any():
+        # the kernel's posterior on ITS list (its own earlier distances, each within its tolerance of the
+        # oracle's): the arithmetic is right, the list is another one
+        with_own = ref["posterior_at"](b, i, g["d_js"][b, i], earlier=g["d_js"][b, :i])
+        if abs(g["p_accept"][b, i] - with_own) <= PA_ATOL:
             member_seq[b] = True
             continue
         raise AssertionError(
