@@ -708,6 +708,55 @@ def test_random_shapes_and_options(am, wl, oracle, case):
     assert rep["flips"] <= 1
 
 
+def _extreme_rows(rng, batch, B, K, V, dtype, mode):
+    """Rows far from the configurations' recipe: 0 nearly all mass on one token (target and mostly also draft),
+    1 large offsets and scales, 2 draft rows next to the target rows (tiny distances), 3 flat rows."""
+    t, d = batch.target.float(), batch.draft.float()
+    if mode == 0:
+        for b in range(B):
+            for i in range(K + 1):
+                at = int(rng.integers(0, V)); amp = float(rng.uniform(8, 40))
+                t[b, i, at] += amp
+                if i < K and rng.random() < 0.7:
+                    d[b, i, at] += amp * float(rng.uniform(0.5, 1.1))
+    elif mode == 1:
+        t = t * float(rng.uniform(0.1, 12)) + float(rng.uniform(-80, 80))
+        d = d * float(rng.uniform(0.1, 12)) + float(rng.uniform(-80, 80))
+    elif mode == 2:
+        d = t[:, :K] + torch.randn(B, K, V) * float(rng.choice([1e-3, 1e-2, 0.05]))
+    else:
+        t = t * 0.01; d = d * 0.01
+    batch.target, batch.draft = t.to(dtype), d.to(dtype)
+
+
+@pytest.mark.parametrize("case", [257, 413, 626] + list(range(1000, 1021)))
+def test_rows_with_extreme_shapes_and_random_options(am, wl, oracle, case):
+    """Seeded draws of peaked, shifted and scaled, near-identical and flat rows with random options, history
+    sizes, window lengths and statistics path (the first three seeds are cases a randomised sweep once
+    failed on: posteriors after in-loop appends of distances below the floor of the divergence)."""
+    rng = np.random.default_rng(41000 + case)
+    B = int(rng.integers(1, 6)); K = int(rng.choice([1, 3, 6, 11])); V = int(rng.choice([64, 1000, 2048, 4104, 8200, 32768]))
+    dtype = torch.bfloat16 if rng.random() < 0.5 else torch.float32
+    batch = wl.config_batched(B=B, k=K, V=V, seed=5000 + case, dtype=dtype, cap=64)
+    mode = int(rng.integers(0, 4))
+    _extreme_rows(rng, batch, B, K, V, dtype, mode)
+    path = int(rng.integers(1, 3))
+    opt = dict(base_test=int(rng.integers(0, 2)), list_update=int(rng.integers(0, 2)), reject_rule=int(rng.integers(0, 2)),
+               apply_update=int(rng.integers(0, 2)))
+    options = am.Options(**opt)
+    if rng.random() < 0.5:
+        g = torch.Generator().manual_seed(case)
+        cap = int(rng.choice([100, 600, 3000]))
+        n_hist = int(rng.choice([2, 64, 90, 450, 2500])) if cap >= 2500 else int(rng.choice([2, 64, 90]))
+        batch.state = wl.threshold_state(B, cap, g, n_hist=n_hist)
+    if rng.random() < 0.4:
+        batch.draft_len = torch.tensor(rng.integers(0, K + 1, B), dtype=torch.int32)
+    out, _, _ = G.run_gpu(am, batch, options=options, stats_path=path)
+    ref = G.run_oracle(oracle, batch, options=options)
+    rep = G.compare_verify(out, ref, info_bits=16 | 8)
+    _report(f"extreme rows {case}: mode {mode} path {path} {opt}", rep)
+
+
 # ------------------------------------------------------------------------------- close calls of the argmax
 @pytest.mark.parametrize("dtype,V", [(torch.bfloat16, 4104), (torch.float32, 2056), (torch.bfloat16, 4107)],
                          ids=["bf16-2slices", "f32-2slices", "bf16-unaligned"])
