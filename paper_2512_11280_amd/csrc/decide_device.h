@@ -27,6 +27,11 @@ __device__ __forceinline__ double half_max_d(double v) {
   return fmax(v, __shfl_xor(v, 16));
 }
 
+// The lists hold distances strictly inside (d_eps, 1 - d_eps) (Section 4.4 leaves out the values "exactly 0
+// or 1").  1 - d is exact in float from d = 1/2 on, so this is the comparison of the real numbers; 1 - d_eps
+// rounded to float would shut out the float just below it.  NaN fails both.
+__device__ __forceinline__ bool inside_open_interval(float d, float d_eps) { return d > d_eps && 1.0f - d > d_eps; }
+
 struct Kde {
   double inv2h2;   // 1 / (2 h^2)
   double log_norm; // ln(n h sqrt(2 pi)) - ln prior  (subtracted from the log kernel sum)
@@ -216,7 +221,7 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
     __syncthreads();
     if (wave == 0) {
       const float dv = lane < kb ? sh.dist[lane] : NAN;
-      const bool pass = dv > a.d_eps && dv < 1.0f - a.d_eps;      // NaN fails both
+      const bool pass = inside_open_interval(dv, a.d_eps);
       const unsigned long long mask = __ballot(pass);
       const int rank = __popcll(mask & ((1ull << lane) - 1ull));
       if (lane < kb) sh.n_before[lane] = (uint8_t)rank;
@@ -413,9 +418,8 @@ __device__ inline uint32_t update_sequence_core(const UpdateArgs& a, int b, int 
   const int nA = a.nA[b], nR = a.nR[b];
   double ent_sum = a.ent_sum[b];      // (asked for with the lengths: the last lane needs them at the very end)
   int ent_cnt = a.ent_cnt[b];
-  const float lo = a.d_eps, hi = 1.0f - a.d_eps;
   if (!(lane <= r && lane < kb)) d = 0.f;
-  const bool pass = d > lo && d < hi;                       // NaN fails both comparisons
+  const bool pass = inside_open_interval(d, a.d_eps);
   uint32_t st = 0;
   // accepted positions 0 .. r-1
   const unsigned long long acc = __ballot(pass && lane < r);
@@ -676,7 +680,7 @@ __device__ void decide_position_wide(const DecideArgs& a, const UpdateArgs& upd,
       __syncthreads();
       if (wave == 0) {
         const float dv = lane < i ? sh.dist[lane] : NAN;
-        const bool pass = dv > a.d_eps && dv < 1.0f - a.d_eps;
+        const bool pass = inside_open_interval(dv, a.d_eps);
         const unsigned long long mask = __ballot(pass);
         if (pass) sh.extra[__popcll(mask & ((1ull << lane) - 1ull))] = dv;
         if (lane == 0) wsh.n_pass = __popcll(mask);

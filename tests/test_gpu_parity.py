@@ -1036,6 +1036,7 @@ def test_update_matches_oracle_and_state_round_trip(am, wl, oracle, B, K, cap):
         Hq = rng.uniform(0.1, 6.0, (B, K)).astype(np.float32)
         dj = rng.uniform(0.0, 1.0, (B, K)).astype(np.float32)
         dj[0, 0], dj[1, 1], dj[2, 2] = 0.0, 1.0, 5e-7
+        dj[3, 0], dj[4, 0], dj[5, 0] = 1.0 - 1e-6, 1e-6, 0.99999905   # the floats next to the ends of the open interval
         if rnd == 3:
             Hq[4, :] = np.nan
             dj[5, :] = np.nan
