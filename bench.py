@@ -24,8 +24,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the statistics stage on this workload, from the rocprofv3 counter runs kept
 # under profiles/ (FETCH_SIZE and WRITE_SIZE, each scaled by what it reads for a plain copy of known
-# size): k_rowstats 131.63 MB + 0.13 MB, k_jsd 132.94 MB + 0.08 MB.  Only valid for the default path.
-STAGE_TRAFFIC_BYTES = 264.78e6
+# size): k_rowstats 131.38 MB + 0.13 MB, k_jsd 132.04 MB + 0.08 MB.  Only valid for the default path.
+STAGE_TRAFFIC_BYTES = 263.63e6
 # shapes: the headline workload is the one the metric is quoted on; "large" is a side measurement
 WORKLOADS = {"headline": (32, 8, 128256, 4),      # 4 sets x 139.5 MB of logits
              "large": (128, 16, 152064, 2),       # 2 sets x 1.28 GB
