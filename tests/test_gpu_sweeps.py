@@ -200,3 +200,31 @@ def test_strided_and_misaligned_views_sweep(am, wl, oracle, case):
     assert np.array_equal(tok.cpu().numpy(), ref_tok), (tok.cpu().numpy(), ref_tok, gap)
     Href, _ = oracle.draft_entropy(batch.draft[:, 0].contiguous(), step=0, k_max=9)
     assert G.close(H.cpu().numpy(), Href).all()
+
+
+# ------------------------------------------------------------------------------------------ one workspace, many shapes
+def test_one_workspace_serves_calls_of_different_shapes(am, wl, oracle):
+    """The regions of a workspace only depend on its size, and every kernel leaves the arrival counters it
+    used at zero: verification calls of different shapes, window lengths, history sizes and options and
+    drafting calls in between, all on ONE workspace, each against the oracle."""
+    rng = np.random.default_rng(4242)
+    dtype = torch.bfloat16
+    ws = am.Workspace(40, 9, 8200, dtype)
+    for call in range(40):
+        B = int(rng.integers(1, 41)); K = int(rng.choice([1, 2, 5, 9])); V = int(rng.choice([64, 1000, 4099, 4104, 8200]))
+        batch = wl.config_batched(B=B, k=K, V=V, seed=9000 + call, dtype=dtype, cap=64)
+        if rng.random() < 0.5:
+            g = torch.Generator().manual_seed(call)
+            batch.state = wl.threshold_state(B, 700, g, n_hist=int(rng.choice([64, 500])))    # both forms of the decision kernel
+        if rng.random() < 0.5:
+            batch.draft_len = torch.tensor(rng.integers(0, K + 1, B), dtype=torch.int32)
+        options = am.Options(stats_path=int(rng.integers(1, 3)), list_update=int(rng.integers(0, 2)),
+                             apply_update=int(rng.integers(0, 2)))
+        out, _, _ = G.run_gpu(am, batch, options=options, ws=ws)
+        G.compare_verify(out, G.run_oracle(oracle, batch, options=options), info_bits=16 | 8)
+        rows = batch.draft[:, 0].contiguous()
+        H, stop, tok, _ = am.draft_step(rows.cuda(), ws, step=0, k_max=4, seed=call, round0=call)
+        ref_tok, gap = oracle.draft_sample(rows, step=0, seed=call, round0=call)
+        assert np.array_equal(tok.cpu().numpy(), ref_tok), (call, tok.cpu().numpy(), ref_tok, gap)
+        Href, _ = oracle.draft_entropy(rows, step=0, k_max=4)
+        assert G.close(H.cpu().numpy(), Href).all(), call
