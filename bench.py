@@ -423,6 +423,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": STAGE_TRAFFIC_BYTES if ("jsd" in kern_us and args.stats_path in (0, 1) and not large) else None,
+                     "traffic_GBps": (STAGE_TRAFFIC_BYTES / (stats_us * 1e-6) / 1e9
+                                      if ("jsd" in kern_us and args.stats_path in (0, 1) and not large and stats_us > 0) else None),
                      "kernel": "k_stats_pipe + k_stats_finish" if "jsd" not in kern_us else "k_rowstats + k_jsd",
                      "algorithmic_bytes": algo_bytes,
                      "kernel_us": stats_us,
