@@ -70,7 +70,7 @@ def run_oracle(oracle, batch, options=None, seq_id=None, rounds=None):
         if kw.get("list_update", 0):
             eps, cap = kw["d_eps"], s["LA"].shape[1]
             for j in range(i):
-                dj = ref["d_js"][b, j] if earlier is None else earlier[j]
+                dj = float(ref["d_js"][b, j] if earlier is None else earlier[j])   # (a float32 scalar would pull 1 - eps down to float32)
                 if eps < dj < 1.0 - eps and len(la) < cap:
                     la.append(np.float32(dj))
         return oracle.posterior(float(d), np.float32(la), s["LR"][b, :int(s["nR"][b])],
