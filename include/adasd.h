@@ -123,12 +123,11 @@ typedef struct {
   int32_t relaxed_off; /* 1: Bayesian test disabled (the "Gen-Only" ablation of Section 5.3) */
   float d_eps;         /* distances <= d_eps or >= 1-d_eps count as "exactly 0 or 1" and are not
                           recorded (Section 4.4); 0 selects the default 1e-6 */
-  int32_t stats_path;  /* kernels of the statistics stage: 0 the library's choice (the two-kernel
-                          path, the faster one on gfx950); 1 the two-kernel path (normalisers, then
-                          JS distance: the logits are read twice); 2 the single-read kernel when
-                          every row is 16-byte aligned and V is a whole number of 16-byte vectors,
-                          else the two-kernel path.  Same results to the documented tolerance either
-                          way. */
+  int32_t stats_path;  /* kernels of the statistics stage: 0 the library's choice; 1 the two-kernel path
+                          (normalisers, then JS distance: the logits are read twice); 2 the single-read
+                          kernel when every row is 16-byte aligned and V is a whole number of 16-byte
+                          vectors of at most 2^18, else the two-kernel path.  Same results to the
+                          documented tolerance either way. */
   int32_t apply_update; /* 1: adasd_verify also applies the round to args->state, exactly as
                           adasd_update_thresholds would with the same d_eps (the decision kernel
                           does it after the sequence's decisions, which saves a launch);
@@ -143,6 +142,11 @@ typedef struct {
                           rejection are reported under the same rule), with the list-size prior
                           counted on the extended list.  The state itself is still only written by
                           the update step, which leaves the same lists either way. */
+  int32_t wait_polls;  /* single-read statistics kernel: how often a workgroup polls for the results of the
+                          other workgroups of its position before it stops waiting and recomputes them
+                          itself (bit-identical results either way).  0: the default (16384, about 25 ms);
+                          negative: do not wait at all, which tests use to exercise the recomputation
+                          without any wave ever spinning. */
 } adasd_options;
 
 /*
@@ -370,15 +374,6 @@ int adasd_profile_disable(void);
  * does nothing.  Enqueues one kernel on `stream`; allocates nothing and does not synchronise.
  */
 int adasd_stream_read(const void *src, size_t bytes, uint32_t *sink, size_t sink_words, void *stream);
-
-/*
- * Test hook for the bounded waits of the single-read statistics kernel (stats_path 2): a workgroup
- * polls for the other workgroups' results at most `polls` times (default 65536, roughly 15 ms)
- * before it stops waiting and recomputes them itself, which gives bit-identical results.  0 makes
- * every workgroup take that path at once; tests use it to exercise the path without any wave ever
- * spinning for long.
- */
-int adasd_set_spin_limit(int polls);
 
 const char *adasd_strerror(int code);
 int adasd_version(void);

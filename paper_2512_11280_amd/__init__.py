@@ -6,7 +6,7 @@ marshals torch tensors into that C ABI.  There is no CPU fallback: calls raise i
 not been built (``python -m paper_2512_11280_amd.build`` or ``__graft_entry__.build()``).
 """
 from .binding import (AdasdError, Options, State, VerifyResult, draft_entropy, draft_step, library_path,  # noqa: F401
-                      load_library, profile_disable, profile_enable, profile_read, set_spin_limit, stream_read,
+                      load_library, profile_disable, profile_enable, profile_read, stream_read,
                       update_thresholds, verify, workspace_bytes, Workspace, Shard, verify_shard_stats,
                       verify_shard_jsd, verify_shard_decide, verify_shard_sample, verify_shard_pick,
                       verify_shard_refine, verify_shard_settle)

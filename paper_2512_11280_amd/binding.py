@@ -38,7 +38,8 @@ class _State(C.Structure):
 class _Options(C.Structure):
     _fields_ = [("base_test", C.c_int32), ("reject_rule", C.c_int32), ("kde_min_n", C.c_int32),
                 ("bw_rule", C.c_int32), ("relaxed_off", C.c_int32), ("d_eps", C.c_float),
-                ("stats_path", C.c_int32), ("apply_update", C.c_int32), ("list_update", C.c_int32)]
+                ("stats_path", C.c_int32), ("apply_update", C.c_int32), ("list_update", C.c_int32),
+                ("wait_polls", C.c_int32)]
 
 
 class _VerifyArgs(C.Structure):
@@ -147,11 +148,12 @@ class Options:
     stats_path: int = 0
     apply_update: int = 0
     list_update: int = 0
+    wait_polls: int = 0
 
     def _c(self) -> _Options:
         return _Options(self.base_test, self.reject_rule, self.kde_min_n, self.bw_rule,
                         self.relaxed_off, self.d_eps, self.stats_path, self.apply_update,
-                        self.list_update)
+                        self.list_update, self.wait_polls)
 
 
 def workspace_bytes(B: int, k_max: int, V: int, dtype: torch.dtype) -> int:
@@ -496,10 +498,6 @@ def stream_read(src: torch.Tensor, sink: torch.Tensor):
     rc = load_library().adasd_stream_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(),
                                           sink.numel(), _stream())
     _check(rc, "adasd_stream_read")
-
-
-def set_spin_limit(polls: int):
-    _check(load_library().adasd_set_spin_limit(polls), "adasd_set_spin_limit")
 
 
 def profile_enable(max_launches: int):

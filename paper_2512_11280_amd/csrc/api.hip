@@ -1,5 +1,4 @@
 // C ABI of libadasd: argument validation, workspace carving and kernel enqueue.
-#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -12,8 +11,6 @@ namespace {
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
-
-std::atomic<int> g_spin_limit{1 << 16};
 
 // ---- optional kernel timing ----------------------------------------------------------------
 constexpr int kClasses = 7;
@@ -49,9 +46,7 @@ namespace {
 constexpr size_t kHeaderBytes = (65536 + 32768 + 32768) * sizeof(int32_t);
 // bytes per position of every shape-dependent region (per-sequence regions are sized per position too)
 constexpr size_t kRegionBytes[] = {
-    kCntStride * sizeof(int32_t),                         // fused_cnt
-    (size_t)kMaxFusedSplit * kSlotWords * sizeof(uint64_t),  // fused_slots
-    (size_t)kSlotWords * sizeof(uint64_t),                // fused_norm
+    (size_t)kMaxSplit * kXchgWords * sizeof(uint64_t),    // xchg
     2 * (size_t)kMaxSplit * sizeof(float4),               // part1
     2 * sizeof(RowResult),                                // rows
     (size_t)kMaxSplit * sizeof(float2),                   // part2
@@ -69,11 +64,11 @@ constexpr size_t per_position_bytes() {
 }  // namespace
 
 size_t workspace_bytes_for(size_t positions) {
-  return kHeaderBytes + (positions + 1) * per_position_bytes() + 11 * 256;
+  return kHeaderBytes + (positions + 1) * per_position_bytes() + 9 * 256;
 }
 
 size_t workspace_layout(size_t ws_bytes, Workspace* ws, void* base) {
-  const size_t slack = kHeaderBytes + 11 * 256;
+  const size_t slack = kHeaderBytes + 9 * 256;
   if (ws_bytes <= slack) return 0;
   const size_t cap = (ws_bytes - slack) / per_position_bytes();
   if (ws && cap > 0) {
@@ -88,17 +83,15 @@ size_t workspace_layout(size_t ws_bytes, Workspace* ws, void* base) {
     ws->ticket1 = reinterpret_cast<int32_t*>(take(kTicket1Len * sizeof(int32_t)));
     ws->ticket2 = reinterpret_cast<int32_t*>(take(kTicket2Len * sizeof(int32_t)));
     ws->ticket3 = reinterpret_cast<int32_t*>(take(kTicket3Len * sizeof(int32_t)));
-    ws->fused_cnt = reinterpret_cast<int32_t*>(take(cap * kRegionBytes[0]));
-    ws->fused_slots = reinterpret_cast<uint64_t*>(take(cap * kRegionBytes[1]));
-    ws->fused_norm = reinterpret_cast<uint64_t*>(take(cap * kRegionBytes[2]));
-    ws->part1 = reinterpret_cast<float4*>(take(cap * kRegionBytes[3]));
-    ws->rows = reinterpret_cast<RowResult*>(take(cap * kRegionBytes[4]));
-    ws->part2 = reinterpret_cast<float2*>(take(cap * kRegionBytes[5]));
-    ws->plan = reinterpret_cast<SamplePlan*>(take(cap * kRegionBytes[6]));
-    ws->part3 = reinterpret_cast<Top2*>(take(cap * kRegionBytes[7]));
-    ws->pos_rec = reinterpret_cast<PosRecord*>(take(cap * kRegionBytes[8]));
-    ws->tok = reinterpret_cast<float2*>(take(cap * kRegionBytes[9]));
-    ws->slots = reinterpret_cast<int32_t*>(take(cap * kRegionBytes[10]));
+    ws->xchg = reinterpret_cast<uint64_t*>(take(cap * kRegionBytes[0]));
+    ws->part1 = reinterpret_cast<float4*>(take(cap * kRegionBytes[1]));
+    ws->rows = reinterpret_cast<RowResult*>(take(cap * kRegionBytes[2]));
+    ws->part2 = reinterpret_cast<float2*>(take(cap * kRegionBytes[3]));
+    ws->plan = reinterpret_cast<SamplePlan*>(take(cap * kRegionBytes[4]));
+    ws->part3 = reinterpret_cast<Top2*>(take(cap * kRegionBytes[5]));
+    ws->pos_rec = reinterpret_cast<PosRecord*>(take(cap * kRegionBytes[6]));
+    ws->tok = reinterpret_cast<float2*>(take(cap * kRegionBytes[7]));
+    ws->slots = reinterpret_cast<int32_t*>(take(cap * kRegionBytes[8]));
     ws->bytes = off;
   }
   return cap;
@@ -414,10 +407,21 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   const int B = a->B, K = a->k_max, V = a->V;
   hipStream_t st = (hipStream_t)stream;
   VerifyOut vout{a->H_p, a->H_q, a->d_js, nullptr, nullptr};
-  int fNV = 0, fS = 0;
-  if (K > 0 && opt.stats_path == 2 && fused_plan(map, (int)a->dt, &fNV, &fS)) {
+  int fT = 0, fNB = 0, fS = 0;
+  if (K > 0 && opt.stats_path != 1 && fused_plan(map, (int)a->dt, &fT, &fNB, &fS)) {
     Scope sc(0, st);
-    if (launch_stats_fused(map, (int)a->dt, fNV, fS, g_spin_limit.load(), ws, vout, st) != hipSuccess) return ADASD_ERR_HIP;
+    RowMap smap = map;
+    if (a->draft_len) {          // ragged windows: the positions that have work, packed
+      if (launch_pack_slots(a->draft_len, B, K, ws.slots, st) != hipSuccess) return ADASD_ERR_HIP;
+      smap.slots = ws.slots;
+    }
+    vout.tokens = a->draft_tokens;
+    vout.tok = a->draft_tokens ? ws.tok : nullptr;
+    const int polls = opt.wait_polls == 0 ? kWaitPolls : (opt.wait_polls < 0 ? 0 : opt.wait_polls);
+    if (launch_stats_fused(smap, (int)a->dt, fT, fNB, fS, polls, ws, vout, st) != hipSuccess) return ADASD_ERR_HIP;
+    d.jsd_split = fS;
+    d.xchg_split = fS;
+    d.tok = vout.tok;
   } else if (K > 0) {
     const int rows = B * K * 2;
     const int S = pick_split(rows, V, (int)a->dt);
@@ -617,12 +621,6 @@ int adasd_update_thresholds(const adasd_state* st, int k_max, const int32_t* n_a
   hipStream_t s = (hipStream_t)stream;
   Scope sc(4, s);
   return launch_update(u, s) == hipSuccess ? ADASD_OK : ADASD_ERR_HIP;
-}
-
-int adasd_set_spin_limit(int polls) {
-  if (polls < 0) return ADASD_ERR_INVALID_ARG;
-  g_spin_limit.store(polls);
-  return ADASD_OK;
 }
 
 int adasd_stream_read(const void* src, size_t bytes, uint32_t* sink, size_t sink_words, void* stream) {

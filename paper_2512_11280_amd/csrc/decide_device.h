@@ -161,6 +161,20 @@ __device__ __forceinline__ float fold_distance(const PosLoad& L) {
   return (L.rp.bad || L.rq.bad) ? NAN : (float)sqrt(D);
 }
 
+// The hand-off words that the single-read statistics kernel left for `count` positions from `first` on go
+// back to zero (they are only read inside that kernel, which has finished; the next call finds them clear).
+// The stores are dealt to the threads from the last one backwards: the first wavefront, which carries the
+// latency chains of these kernels, gets none unless there are more than 192 words.
+__device__ __forceinline__ void clear_exchange_words(const DecideArgs& a, const Workspace& ws, size_t first, int count) {
+  if (a.xchg_split <= 0) return;
+  const int per_pos = a.xchg_split * kXchgWords;
+  for (int j = kBlock - 1 - (int)threadIdx.x; j < count * per_pos; j += kBlock) {
+    const int i = j / per_pos, w = j - i * per_pos;
+    __hip_atomic_store(ws.xchg + (first + i) * (size_t)(kMaxSplit * kXchgWords) + w, 0ull, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
 // The decisions of one sequence by one workgroup of 256 threads.  INLOOP: the accepted list grows
 // inside the verification loop (Algorithm 1): position i sees the list of the state followed by the
 // distances of positions 0..i-1 of this round that pass the open-interval filter, up to the capacity.
@@ -399,6 +413,7 @@ __device__ void decide_sequence(const DecideArgs& a, const Workspace& ws, int b,
     sh.first_reject = r;
     sh.k_b = kb;
   }
+  clear_exchange_words(a, ws, (size_t)b * K, K);
   __syncthreads();
 }
 
@@ -836,6 +851,7 @@ __device__ void decide_position_wide(const DecideArgs& a, const UpdateArgs& upd,
     wsh.last = ticket == K - 1;
   }
   __syncthreads();
+  clear_exchange_words(a, ws, o, 1);
   if (!wsh.last || wave != 0) return;
 
   // ---- last workgroup of the sequence, one wavefront, one lane per position

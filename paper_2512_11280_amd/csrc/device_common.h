@@ -162,13 +162,18 @@ __device__ __forceinline__ float wave_sum_f(float v) {
   v += dpp_rot<0x128>(v);    // row_ror:8
   return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
 }
+// (The maximum is written as one data-parallel instruction per step: from the builtin the compiler makes a
+// move, a canonicalising maximum and the maximum itself.  A data-parallel operand must not be read in the two
+// instruction slots after the instruction that wrote it, hence the s_nop.)
+#define ADASD_DPP_MAX(v, ROT) asm("s_nop 1\n\tv_max_f32_dpp %0, %0, %0 " ROT " row_mask:0xf bank_mask:0xf" : "+v"(v))
 __device__ __forceinline__ float wave_max_f(float v) {
-  v = fmaxf(v, dpp_rot<0x121>(v));
-  v = fmaxf(v, dpp_rot<0x122>(v));
-  v = fmaxf(v, dpp_rot<0x124>(v));
-  v = fmaxf(v, dpp_rot<0x128>(v));
+  ADASD_DPP_MAX(v, "row_ror:1");
+  ADASD_DPP_MAX(v, "row_ror:2");
+  ADASD_DPP_MAX(v, "row_ror:4");
+  ADASD_DPP_MAX(v, "row_ror:8");
   return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
 }
+#undef ADASD_DPP_MAX
 
 __device__ __forceinline__ uint32_t pk_max_f16(uint32_t a, uint32_t b) {
   uint32_t r;
@@ -233,10 +238,23 @@ __device__ __forceinline__ void lse_accum(const uint4& v, float m, float& s0, fl
 
 // Cross-workgroup hand-off without a cache write-back.  An agent-scope fence on gfx950 writes back
 // and invalidates the XCD's whole L2, which serialises badly when every workgroup does it.  Instead
-// the few words that travel between workgroups are written and read with agent-scope atomic
-// accesses (they bypass the non-coherent cache levels), the writer waits for its stores to complete
-// (publish_barrier) before it bumps the arrival counter, and the reader only issues its loads after
-// the counter's value has come back (control dependency).
+// every word that travels between workgroups is written and read with agent-scope ATOMIC accesses, the
+// writer waits for its stores to complete (publish_barrier) before it bumps the arrival counter, and the
+// reader only issues its loads after the counter's value has come back (control dependency).
+//
+// Why that is enough, also between workgroups on different XCDs (whose L2 caches are not coherent with
+// each other).  The code sequences the memory model prescribes for a release and an acquire at agent
+// scope are "write back L2; wait for all memory operations; atomic" and "atomic; invalidate L1/L2".  The
+// write-back and the invalidate exist for the ORDINARY stores and loads around the atomic: ordinary data
+// may sit dirty in the writer's L2 or stale in the reader's caches.  An agent-scope atomic store itself is
+// performed at the memory side of the L2s (it is written through), and an agent-scope atomic load never
+// takes a line from a cache that is not coherent at that scope.  Here the payload consists of such
+// accesses only, so nothing is left for the cache maintenance to do; what remains of the release is the
+// wait for the payload stores to have completed before the counter's read-modify-write is issued
+// (s_waitcnt 0 below: a write-through store counts as complete when the memory side has acknowledged it),
+// and what remains of the acquire is that the payload loads are issued after the counter's value is known,
+// which the branch on that value and the in-order issue of a wavefront give.  The single-read statistics
+// kernel does not even need that much: its words carry their own validity (stats_fused.hip).
 __device__ __forceinline__ void st_agent(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

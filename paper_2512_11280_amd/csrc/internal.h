@@ -17,9 +17,8 @@ constexpr int kWideMin = 384;       // list length from which a sequence actuall
 constexpr int kNarrowMax = kWideCap; // so the one-workgroup form never sees a longer list: it stages both in shared memory
 constexpr int kMaxSplit = 64;        // vocabulary slices per row (statistics kernels)
 constexpr int kMaxSampleSplit = 128; // vocabulary slices per sequence (sampling kernel)
-constexpr int kMaxFusedSplit = 128;  // wavefront slices per row pair in the fused statistics kernel
-constexpr int kSlotWords = 4;        // 64-bit words per (position, slice) of the fused kernel
-constexpr int kCntStride = 32;       // ints between the counters of two positions (one 128-byte line each)
+constexpr int kXchgWords = 3;        // 64-bit hand-off words per (position, slice) of the single-read statistics kernel
+constexpr int kWaitPolls = 16384;    // polls (about 25 ms) before a workgroup of that kernel stops waiting for the others
 
 // Where the rows of one call live.  which = 0: target, 1: draft.
 struct RowMap {
@@ -42,9 +41,8 @@ struct Workspace {
   SamplePlan* plan;   // [B]
   Top2* part3;        // [B][kMaxSampleSplit]
   int32_t* ticket3;   // [kTicket3Len]       arrival counters of the sampling kernel, zero between calls
-  int32_t* fused_cnt; // [positions][kCntStride] arrival counters of the fused kernel, one per 128-byte line
-  uint64_t* fused_slots; // [positions][kMaxFusedSplit][kSlotWords] self-validating hand-off words, zero between calls
-  uint64_t* fused_norm;  // [positions][kSlotWords] folded triples of both rows, published by the position's leader
+  uint64_t* xchg;     // [positions][kMaxSplit][kXchgWords] self-validating hand-off words of the single-read statistics
+                      // kernel (two floats each, valid flag in the lowest mantissa bit of the low one), zero between calls
   PosRecord* pos_rec; // [positions] outcomes of the positions (long-history decision kernel)
   float2* tok;        // [positions] logits of the drafted tokens (looked up by the JS kernel or by the column shards)
   int32_t* slots;     // [positions] packed list of the positions inside their windows (ragged calls)
@@ -120,8 +118,11 @@ size_t stream_read_groups(size_t bytes);
 hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t st);
 
 hipError_t launch_rowstats(const RowMap& map, int dt, int rows, int S, const Workspace& ws, hipStream_t st);
-bool fused_plan(const RowMap& map, int dt, int* NV_out, int* S_out);
-hipError_t launch_stats_fused(const RowMap& map, int dt, int NV, int S, int spin_limit,
+// Single-read statistics kernel: T threads per workgroup, NB vectors per thread and row, S slices per position.
+// It leaves what the two-kernel path leaves (rows, entropies, per-slice JS sums, the drafted tokens' logits)
+// plus the hand-off words of the positions it worked on, which the decision kernel clears (DecideArgs::xchg_split).
+bool fused_plan(const RowMap& map, int dt, int* T_out, int* NB_out, int* S_out);
+hipError_t launch_stats_fused(const RowMap& map, int dt, int T, int NB, int S, int wait_polls,
                               const Workspace& ws, const VerifyOut& vout, hipStream_t st);
 
 struct UpdateArgs {
@@ -145,6 +146,7 @@ struct DecideArgs {
   RowMap map;
   int32_t dt;
   int32_t jsd_split;   // > 0: the distances are still per-slice partial sums of the JS kernel (that many per position)
+  int32_t xchg_split;  // > 0: the single-read statistics kernel ran with that many slices: its hand-off words are cleared here
   const int32_t* draft_tokens;
   // state (device pointers, may be null)
   int32_t cap;

@@ -6,6 +6,8 @@
 // of the second kernel folds the slices of its two rows itself (same code, same order, so the same
 // normalisers everywhere) and leaves one partial JS sum per position and slice, which the decision
 // kernel adds up in slice order.  Kernel boundaries are the only synchronisation.
+#include <type_traits>
+
 #include "stats_device.h"
 
 namespace adasd {
@@ -111,24 +113,8 @@ k_rowstats(RowMap map, int S, Workspace ws) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Pass 2: JS divergence.  Per element, with b = max(p,q), r = min(p,q)/max(p,q) = 2^-|delta| and
-// delta = log2 q - log2 p,
-//     p log2(p/m) + q log2(q/m) = b * ( r * log2 r - (1 + r) * log2((1 + r)/2) ),   m = (p+q)/2,
-// which is non-negative, symmetric in (p,q), never overflows (r <= 1), and keeps every logarithm
-// at magnitude <= 1 so the hardware log's absolute error stays at the 1e-7 level even when the
-// probabilities themselves are 2^-17.  delta is formed from the exact logit difference.
+// Pass 2: JS divergence (the per-element term is jsd_push in stats_device.h).
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void jsd_push(float zp, float zq, float cp, float cq, float dc, float& acc) {
-  float yp = fmaf(zp, kLog2e, -cp), yq = fmaf(zq, kLog2e, -cq);   // log2 p, log2 q
-  float b = ex2(fmaxf(yp, yq));
-  float delta = fmaf(zq - zp, kLog2e, -dc);
-  float nd = fmaxf(-fabsf(delta), -126.0f);   // masked logits (delta = +-inf or NaN) end up at r = 2^-126
-  float r = ex2(nd);
-  float h = fmaf(r, 0.5f, 0.5f);
-  float t = fmaf(-2.0f, h * lg2(h), r * nd);
-  acc = fmaf(b, t, acc);
-}
-
 template <int DT, int kJsdBatch>   // kJsdBatch: vector pairs per thread and batch
 __global__ void __launch_bounds__(kBlock)
 k_jsd(RowMap map, int S, int S_fold, Workspace ws, VerifyOut vout) {
@@ -192,35 +178,43 @@ k_jsd(RowMap map, int S, int S_fold, Workspace ws, VerifyOut vout) {
     zx_p = load_elem_bits<DT>(rp.ptr, x);
     zx_q = load_elem_bits<DT>(rq.ptr, x);
   }
-  const float cp = (float)resp.lse2, cq = (float)resq.lse2;
-  const float dc = (float)(resq.lse2 - resp.lse2);
+  const JsNorm n = js_norm(resp, resq);
   float acc = 0.f;
-  if (bad) {
-    // nothing to add up: the decision kernel reports the distance as NaN
-  } else if (vec_path) {
-    float acc1 = 0.f;
-    for (int base = v0; base < v1; base += kJsdBatch * kBlock) {
-      if (base != v0) load_batch(base);
+  // (the same loops twice: rows whose normalisers are far apart take the longer form of the term)
+  auto add_up = [&](auto far_tag) {
+    constexpr bool FAR = decltype(far_tag)::value;
+    if (vec_path) {
+      float acc1 = 0.f;
+      for (int base = v0; base < v1; base += kJsdBatch * kBlock) {
+        if (base != v0) load_batch(base);
 #pragma unroll
-      for (int j = 0; j < kJsdBatch; ++j) {
-        float zp[EPV], zq[EPV];
-        unpack<DT>(xp[j], zp);
-        unpack<DT>(xq[j], zq);
+        for (int j = 0; j < kJsdBatch; ++j) {
+          float zp[EPV], zq[EPV];
+          unpack<DT>(xp[j], zp);
+          unpack<DT>(xq[j], zq);
 #pragma unroll
-        for (int e = 0; e < EPV; e += 2) {
-          jsd_push(zp[e], zq[e], cp, cq, dc, acc);
-          jsd_push(zp[e + 1], zq[e + 1], cp, cq, dc, acc1);
+          for (int e = 0; e < EPV; e += 2) {
+            jsd_push<FAR>(zp[e], zq[e], n, acc);
+            jsd_push<FAR>(zp[e + 1], zq[e + 1], n, acc1);
+          }
         }
       }
+      acc += acc1;
+      if (s == S - 1 && tid == 0)
+        for (int v = nv * EPV; v < V; ++v)
+          jsd_push<FAR>(load_elem<DT>(rp.ptr, v), load_elem<DT>(rq.ptr, v), n, acc);
+    } else {
+      const int e0 = (int)(((int64_t)s * V) / S), e1 = (int)(((int64_t)(s + 1) * V) / S);
+      for (int v = e0 + tid; v < e1; v += kBlock)
+        jsd_push<FAR>(load_elem<DT>(rp.ptr, v), load_elem<DT>(rq.ptr, v), n, acc);
     }
-    acc += acc1;
-    if (s == S - 1 && tid == 0)
-      for (int v = nv * EPV; v < V; ++v)
-        jsd_push(load_elem<DT>(rp.ptr, v), load_elem<DT>(rq.ptr, v), cp, cq, dc, acc);
+  };
+  if (bad) {
+    // nothing to add up: the decision kernel reports the distance as NaN
+  } else if (n.far) {
+    add_up(std::true_type{});
   } else {
-    const int e0 = (int)(((int64_t)s * V) / S), e1 = (int)(((int64_t)(s + 1) * V) / S);
-    for (int v = e0 + tid; v < e1; v += kBlock)
-      jsd_push(load_elem<DT>(rp.ptr, v), load_elem<DT>(rq.ptr, v), cp, cq, dc, acc);
+    add_up(std::false_type{});
   }
 
   acc = wave_sum_f(acc);

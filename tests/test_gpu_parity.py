@@ -30,8 +30,14 @@ def path(request):
     return request.param
 
 
+def _no_flips(rep):
+    """On the five configurations of the benchmark no decision sits within 1e-5 of its threshold: every
+    sequence is compared bit for bit."""
+    assert rep["flips"] == 0 and rep["member_flips"] == 0 and rep["seq_skipped"] == 0, rep
+
+
 def _report(name, rep):
-    print(f"[parity] {name}: flips={rep['flips']} member_flips={rep['member_flips']} unresolved={rep['unresolved']} "
+    print(f"[parity] {name}: flips={rep['flips']} member_flips={rep['member_flips']} "
           f"skipped_seq={rep['seq_skipped']} exact_path={rep['exact_path']} max_rel_H={rep['max_rel_H']:.2e} "
           f"max_rel_d={rep['max_rel_d']:.2e}", flush=True)
 
@@ -42,7 +48,7 @@ def test_config_tiny_fp32(am, wl, oracle, path):
     out, _, _ = G.run_gpu(am, batch, stats_path=path)
     rep = G.compare_verify(out, G.run_oracle(oracle, batch))
     _report("tiny", rep)
-    assert rep["flips"] == 0
+    _no_flips(rep)
 
 
 @pytest.mark.parametrize("with_state", [True, False])
@@ -53,6 +59,7 @@ def test_config_single_stream_bf16(am, wl, oracle, with_state, path):
     ref = G.run_oracle(oracle, batch)
     rep = G.compare_verify(out, ref)
     _report(f"single_stream(state={with_state})", rep)
+    _no_flips(rep)
     # both entropy regimes are present
     assert ref["H_q"][0, :4].max() < ref["H_q"][0, 4:].min()
     # draft-side entropy of each draft row, with a threshold in the middle of the two regimes
@@ -73,6 +80,7 @@ def test_config_batched_reduced(am, wl, oracle, path):
     ref = G.run_oracle(oracle, batch)
     rep = G.compare_verify(out, ref)
     _report("batched(B=8)", rep)
+    _no_flips(rep)
     assert 0 < ref["n_accept"].mean() < 8
     assert (ref["accept_mask"] == 2).any()      # the Bayesian test decides some positions
 
@@ -83,6 +91,7 @@ def test_config_large_reduced(am, wl, oracle, path):
     ref = G.run_oracle(oracle, batch)
     rep = G.compare_verify(out, ref)
     _report("large(B=6,k=16,V=152064)", rep)
+    _no_flips(rep)
 
 
 def test_headline_workload_full_size(am, wl, oracle, path):
@@ -93,6 +102,7 @@ def test_headline_workload_full_size(am, wl, oracle, path):
     ref = G.run_oracle(oracle, batch)
     rep = G.compare_verify(out, ref)
     _report("headline(B=32,k=8,V=128256)", rep)
+    _no_flips(rep)
     assert 0 < ref["n_accept"].mean() < 8
 
 
@@ -116,6 +126,7 @@ def test_large_workload_full_size_sampled_sequences(am, wl, oracle):
         setattr(got, name, getattr(out, name)[pick])
     rep = G.compare_verify(got, ref)
     _report("large(B=128,k=16,V=152064), 8 sampled sequences", rep)
+    _no_flips(rep)
 
 
 def test_largest_window(am, wl, oracle, path):
@@ -232,7 +243,7 @@ def test_nearly_identical_distributions(am, wl, oracle, path):
     d = torch.empty(1, K, V)
     for i, noise in enumerate([0.2, 0.05, 0.01]):                     # flat, std 1
         d[0, i] = t[0, i] + noise * torch.randn(V, generator=g)
-    for i, (zt, zd) in enumerate([(19.0, 18.0), (22.0, 21.9), (25.0, 25.0)], start=3):   # peaked
+    for i, (zt, zd) in enumerate([(19.0, 18.0), (22.0, 21.875), (25.0, 25.0)], start=3):   # peaked
         d[0, i] = t[0, i] + 0.3 * torch.randn(V, generator=g)
         t[0, i, 1000 + i] = zt
         d[0, i, 1000 + i] = zd
@@ -243,10 +254,37 @@ def test_nearly_identical_distributions(am, wl, oracle, path):
     print("[small d] oracle d:", ref["d_js"][0], "gpu d:", out.d_js[0].cpu().numpy(), flush=True)
     rep = G.compare_verify(out, ref)
     _report("nearly identical", rep)
-    assert ref["d_js"].min() < 0.02
-    errD = np.abs(out.d_js[0].cpu().numpy().astype(np.float64) ** 2 - ref["d_js"][0] ** 2)
-    print("[small d] abs error of the divergence (bits):", errD, flush=True)
-    assert errD.max() < 1e-7
+    assert ref["d_js"].min() < 1e-3
+    # small distances keep RELATIVE accuracy (no absolute floor): the per-element term is taken from its
+    # series in the exactly formed log ratio where that ratio is small
+    rel = np.abs(out.d_js[0].cpu().numpy().astype(np.float64) - ref["d_js"][0]) / ref["d_js"][0]
+    print("[small d] relative error of the distance:", rel, flush=True)
+    assert rel.max() < 1e-5
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_rows_with_normalisers_far_apart(am, wl, oracle, dtype, path):
+    """Softmax does not see a row's offset, so the two rows of a position may carry very different ones
+    (hundreds of nats in float32; in bf16 as far as its grid still resolves the row).  The log ratio of an
+    element is then formed from each logit relative to its own row's offset, with the rounding error of the
+    difference carried along, so the distance keeps its accuracy, also where the distributions are close."""
+    V, K = 32768, 4
+    g = torch.Generator().manual_seed(40)
+    t = 3.0 * torch.randn(1, K + 1, V, generator=g)
+    d = torch.empty(1, K, V)
+    cases = [(600.0, 0.5), (-450.0, 0.05), (90.0, 1.5), (1000.0, 0.01)] if dtype == torch.float32 else \
+        [(64.0, 0.5), (-96.0, 0.3), (24.0, 1.0), (-40.0, 0.2)]
+    for i, (shift, noise) in enumerate(cases):
+        d[0, i] = t[0, i] + noise * torch.randn(V, generator=g) + shift
+    tok = torch.full((1, K), 17, dtype=torch.int32)
+    batch = wl.VerifyBatch(t.to(dtype), d.to(dtype), tok, None, wl.empty_state(1, 8), 5)
+    out, _, _ = G.run_gpu(am, batch, stats_path=path)
+    ref = G.run_oracle(oracle, batch)
+    rel = np.abs(out.d_js[0].cpu().numpy().astype(np.float64) - ref["d_js"][0]) / ref["d_js"][0]
+    print(f"[offset rows {dtype}] d:", ref["d_js"][0], "relative error:", rel, flush=True)
+    rep = G.compare_verify(out, ref)
+    _report("offset rows", rep)
+    assert rel.max() < 1e-5
 
 
 # ------------------------------------------------------------------------------- options
@@ -339,7 +377,7 @@ def test_literal_variant_with_the_update_in_the_same_call(am, wl, oracle):
     host = {k: np.array(v, copy=True) for k, v in batch.state.items()}
     oracle.update(host, ref["n_accept"], batch.draft_len.numpy(), ref["H_q"], ref["d_js"], batch.k, d_eps=1e-6)
     got = st.to_host()
-    if rep["flips"] == 0 and rep["unresolved"] == 0:
+    if rep["flips"] == 0 and rep["member_flips"] == 0:
         for k in ("nA", "nR", "ent_cnt"):
             assert np.array_equal(got[k], host[k]), k
 
@@ -1188,7 +1226,7 @@ def test_closed_loop_rounds_against_oracle(am, wl, oracle, mode):
         am.update_thresholds(dev, W, out.n_accept, out.H_q, out.d_js, draft_len=dl_gpu)
         got_before = dev.to_host()
         oracle.update(host, ref["n_accept"], dl_ref, ref["H_q"], ref["d_js"], W)
-        if rep["flips"] == 0 and rep["unresolved"] == 0:
+        if rep["flips"] == 0 and rep["member_flips"] == 0:
             assert np.array_equal(got_before["nA"], host["nA"]) and np.array_equal(got_before["nR"], host["nR"])
             assert np.allclose(got_before["T_G"], host["T_G"], rtol=1e-5)
             for b in range(B):
@@ -1285,16 +1323,12 @@ def test_stream_read_touches_every_byte_once(am, n_bytes):
 
 
 def test_bounded_wait_expiry_gives_identical_results(am, wl):
-    """With a spin limit of 0 every workgroup of the single-read kernel stops waiting at once and
+    """With options.wait_polls < 0 every workgroup of the single-read kernel stops waiting at once and
     recomputes the other slices' results itself; the outputs must not change by a single bit."""
     batch = wl.config_batched(B=4, k=4, V=128256, seed=321)
     a, _, ws = G.run_gpu(am, batch, stats_path=2)
     snap = {k: getattr(a, k).clone() for k in ("n_accept", "next_token", "H_p", "H_q", "d_js", "p_accept")}
-    am.set_spin_limit(0)
-    try:
-        b, _, _ = G.run_gpu(am, batch, ws=ws, stats_path=2)
-    finally:
-        am.set_spin_limit(1 << 16)
+    b, _, _ = G.run_gpu(am, batch, ws=ws, options=am.Options(wait_polls=-1), stats_path=2)
     for k, v in snap.items():
         assert torch.equal(getattr(b, k), v, ), k
     c, _, _ = G.run_gpu(am, batch, ws=ws, stats_path=2)   # and the workspace is clean afterwards

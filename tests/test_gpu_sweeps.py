@@ -157,7 +157,7 @@ def test_history_list_shapes_sweep(am, wl, oracle, case):
     out, dev, _ = G.run_gpu(am, batch, options=options)
     ref = G.run_oracle(oracle, batch, options=options)
     rep = G.compare_verify(out, ref, info_bits=16 | 8)
-    if opt["apply_update"] and rep["flips"] == 0 and rep["unresolved"] == 0:
+    if opt["apply_update"] and rep["flips"] == 0 and rep["member_flips"] == 0:
         host = {k: np.array(v, copy=True) for k, v in st.items()}
         dl = None if batch.draft_len is None else batch.draft_len.numpy()
         oracle.update(host, ref["n_accept"], dl, ref["H_q"], ref["d_js"], K, d_eps=1e-6)
