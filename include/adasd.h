@@ -253,6 +253,23 @@ int adasd_verify(const adasd_verify_args *args /* host */, const adasd_options *
                  void *stream);
 
 /*
+ * adasd_verify for callers that cannot allocate device memory or pass a workspace: code that runs under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels
+ * and bit-identical results; args->workspace and args->ws_bytes are ignored, the scratch memory is an
+ * array of ADASD_NOALLOC_SCRATCH_BYTES inside the library's device image (every GPU the library runs on
+ * holds its own copy until the process ends).  Calls no hipMalloc / hipFree or any allocating routine.
+ * Limit: adasd_workspace_bytes(B, k_max, V, dt) must not exceed ADASD_NOALLOC_SCRATCH_BYTES (about 1200
+ * candidate positions B * k_max), else ADASD_ERR_CAPACITY and nothing is launched.  All calls on one GPU
+ * share that GPU's array: they must be ordered (one stream, or events between streams); calls that
+ * overlap on one GPU race.  The first call on a GPU, and the first after a call that returned
+ * ADASD_ERR_HIP, zeroes the array with a fill kernel on `stream`; after that every kernel leaves the
+ * counters and hand-off words it used at zero, as with a caller's workspace.
+ */
+#define ADASD_NOALLOC_SCRATCH_BYTES ((size_t)8 << 20)
+int adasd_verify_noalloc(const adasd_verify_args *args /* host */, const adasd_options *opt /* host, may be NULL */,
+                         void *stream);
+
+/*
  * Column-sharded verification.  With a tensor-parallel output layer every holder g of G has the columns
  * col_begin_g .. col_begin_g + V_g - 1 of every logit row.  The statistics of Appendix A and Section 2.2
  * are sums over the vocabulary, so each holder forms partial results over its own columns and only small

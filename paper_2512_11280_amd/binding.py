@@ -87,6 +87,7 @@ def load_library():
                                       C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_size_t, C.c_void_p]
     L.adasd_verify.argtypes = [C.POINTER(_VerifyArgs), C.POINTER(_Options), C.c_void_p]
+    L.adasd_verify_noalloc.argtypes = [C.POINTER(_VerifyArgs), C.POINTER(_Options), C.c_void_p]
     L.adasd_verify_shard_stats.argtypes = [C.POINTER(_VerifyArgs), C.POINTER(_Shard), C.c_void_p, C.c_void_p]
     L.adasd_verify_shard_jsd.argtypes = [C.POINTER(_VerifyArgs), C.POINTER(_Shard), C.c_void_p, C.c_void_p,
                                          C.c_void_p]
@@ -289,11 +290,13 @@ def alloc_verify_result(B: int, K: int, device="cuda") -> VerifyResult:
 
 
 def verify(target_logits: torch.Tensor, draft_logits: torch.Tensor, draft_tokens: torch.Tensor,
-           workspace: Workspace, state: Optional[State] = None, draft_len: Optional[torch.Tensor] = None,
+           workspace: Optional[Workspace], state: Optional[State] = None, draft_len: Optional[torch.Tensor] = None,
            seed: int = 0, seq_id: Optional[torch.Tensor] = None, rounds: Optional[torch.Tensor] = None,
            round0: int = 0, options: Optional[Options] = None,
            out: Optional[VerifyResult] = None) -> VerifyResult:
-    """adasd_verify on target_logits [B, k+1, V], draft_logits [B, k, V], draft_tokens [B, k]."""
+    """adasd_verify on target_logits [B, k+1, V], draft_logits [B, k, V], draft_tokens [B, k].
+    workspace=None: adasd_verify_noalloc (the library's built-in scratch array; `out` should then be
+    given too, so that the call allocates nothing at all)."""
     if target_logits.dim() != 3 or draft_logits.dim() != 3:
         raise ValueError("logits must be [B, k(+1), V]")
     B, K1, V = target_logits.shape
@@ -319,8 +322,13 @@ def verify(target_logits: torch.Tensor, draft_logits: torch.Tensor, draft_tokens
         seed & 0xFFFFFFFFFFFFFFFF, _p(seq_id), _p(rounds), round0 & 0xFFFFFFFF,
         out.n_accept.data_ptr(), out.next_token.data_ptr(), out.H_p.data_ptr(), out.H_q.data_ptr(),
         out.d_js.data_ptr(), out.p_accept.data_ptr(), out.accept_mask.data_ptr(),
-        out.status.data_ptr(), workspace.ptr, workspace.bytes)
+        out.status.data_ptr(), workspace.ptr if workspace is not None else None,
+        workspace.bytes if workspace is not None else 0)
     opt = options._c() if options is not None else None
+    if workspace is None:
+        rc = load_library().adasd_verify_noalloc(C.byref(a), C.byref(opt) if opt is not None else None, _stream())
+        _check(rc, "adasd_verify_noalloc")
+        return out
     rc = load_library().adasd_verify(C.byref(a), C.byref(opt) if opt is not None else None, _stream())
     _check(rc, "adasd_verify")
     return out

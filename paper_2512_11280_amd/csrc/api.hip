@@ -457,6 +457,67 @@ int adasd_verify(const adasd_verify_args* a, const adasd_options* opt_in, void* 
   return ADASD_OK;
 }
 
+// ---- verification without a caller-provided workspace -------------------------------------------
+// For callers that cannot allocate device memory (code under HIP graph capture, serving loops and harnesses
+// that forbid hipMalloc): the workspace is an array in the library's own device image.  Every GPU the
+// library runs on holds its own copy of the array at its own address until the process ends; the array's
+// name is only a host-side handle, so its device address is looked up once per device, with that device
+// current, and only that address is ever handed to a kernel.
+constexpr size_t kScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct StaticScratch {
+  std::mutex mu;
+  void* ptr[kMaxDevices] = {};
+  bool clean[kMaxDevices] = {};      // false: the counters and hand-off words have to be zeroed before the next call
+} g_scratch;
+
+// The device address of `scratch` on the current device (looked up on the first call there), zeroed on the
+// caller's stream if it has never been used or if the last call on it failed half-way.
+int static_scratch(void** out, hipStream_t st) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ADASD_ERR_HIP;
+  std::lock_guard<std::mutex> lk(g_scratch.mu);
+  if (!g_scratch.ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ADASD_ERR_HIP;
+    g_scratch.ptr[dev] = p;
+    g_scratch.clean[dev] = false;
+  }
+  if (!g_scratch.clean[dev]) {
+    if (launch_zero(g_scratch.ptr[dev], kScratchBytes, st) != hipSuccess) return ADASD_ERR_HIP;
+    g_scratch.clean[dev] = true;
+  }
+  *out = g_scratch.ptr[dev];
+  return ADASD_OK;
+}
+void static_scratch_failed() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return;
+  std::lock_guard<std::mutex> lk(g_scratch.mu);
+  g_scratch.clean[dev] = false;
+}
+}  // namespace
+
+int adasd_verify_noalloc(const adasd_verify_args* a, const adasd_options* opt, void* stream) {
+  if (!a) return ADASD_ERR_INVALID_ARG;
+  size_t need = 0;
+  int rc = adasd_workspace_bytes(a->B, a->k_max, a->V, a->dt, &need);
+  if (rc) return rc;
+  if (need > kScratchBytes) return ADASD_ERR_CAPACITY;      // more positions than the built-in workspace serves
+  void* ptr = nullptr;
+  rc = static_scratch(&ptr, (hipStream_t)stream);
+  if (rc) return rc;
+  adasd_verify_args b = *a;
+  b.workspace = ptr;
+  b.ws_bytes = kScratchBytes;
+  rc = adasd_verify(&b, opt, stream);
+  if (rc == ADASD_ERR_HIP) static_scratch_failed();         // a launch failed half-way: counters may be left set
+  return rc;
+}
+
 // ---- column-sharded verification ---------------------------------------------------------------
 static int check_shard(const adasd_shard* sh, int V_local, bool local) {
   if (!sh) return ADASD_ERR_INVALID_ARG;
