@@ -33,11 +33,13 @@
  *   - units: entropies in nats; the Jensen-Shannon distance is reported as
  *     d = sqrt(D_JS / ln 2), i.e. the base-2 normalisation under which the paper
  *     states the [0,1] bound and the "exactly 0 or 1" exclusion (Sections 2.2, 4.4);
- *   - accuracy: entropies and distances to 1e-5 relative, with absolute floors of 1e-6 nats on an
- *     entropy and 2e-7 on the squared distance (float arithmetic on probabilities of total mass 1).
- *     The two rows of a position may carry different offsets (softmax does not see them); the
- *     distance keeps that accuracy while their log-normalisers differ by less than 44 nats, beyond
- *     that its relative error grows with the difference (4e-5 at 400 nats).
+ *   - accuracy: every entropy and every distance within 1e-5 |x| + 1e-6 of its exact value x (float
+ *     arithmetic on probabilities of total mass 1; sums in a fixed order, so results are reproducible bit
+ *     for bit).  That holds down to distances of 1e-3 and below, where it is a relative bound (each term
+ *     of the distance is formed from the exact difference of the two logits, and small differences go
+ *     through a series instead of through logarithms that cancel), and whatever offsets the two rows of a
+ *     position carry (softmax does not see them): rows whose log-normalisers lie far apart take a
+ *     compensated form of the same term.
  */
 #ifndef ADASD_H
 #define ADASD_H
@@ -370,10 +372,15 @@ int adasd_update_thresholds(const adasd_state *st /* host */, int k_max, const i
  * hand one pair to each kernel launch (the dispatch stamps them at its start and end, so the
  * durations hold no launch or queueing time); adasd_profile_read waits for the recorded events and
  * returns the summed duration and the number of kernels of one class since the last enable;
- * adasd_profile_disable frees the events.  Kernel classes: 0 row statistics (normalisers + entropy;
- * with stats_path 2 the single-read kernel and its finalisation, class 1 then stays empty),
+ * adasd_profile_disable frees the events.  Kernel classes: 0 row statistics (normalisers + entropy; on
+ * the single-read path the one kernel of the whole statistics stage, class 1 then stays empty),
  * 1 JS distance (two-kernel path), 2 decision, 3 token sampling, 4 state update, 5 drafting calls
  * (adasd_draft_entropy and adasd_draft_step: one kernel per call), 6 adasd_stream_read.
+ * NOT thread-safe: there is one set of events per process, and while it is enabled every entry point
+ * records into it.  Enable, the calls to be timed, read and disable must all come from one thread, with
+ * no other thread inside the library meanwhile.  With timing disabled (the initial state) the entry
+ * points share no mutable host state and may be called from several threads, each on its own stream
+ * and workspace (adasd_verify_noalloc: see there).
  */
 int adasd_profile_enable(int max_launches);
 int adasd_profile_read(int kernel_class, double *total_ms /* host */, int *launches /* host */);
@@ -383,9 +390,8 @@ int adasd_profile_disable(void);
  * Diagnostics for benchmarks: reads `bytes` bytes of device memory at `src` once, with 128-bit loads
  * in the launch shape of the statistics kernels (one workgroup per 32 KiB), and does nothing with them
  * beyond folding them into one word per workgroup, written to sink[0 .. ceil(bytes / 32768)).  Its
- * duration (kernel class 6) is the rate at which the chip streams logits to a kernel without
- * arithmetic: the practical ceiling beside which the bandwidth of the statistics kernels (Appendix A
- * and Section 2.2 of the paper: entropy and JS distance over the whole vocabulary) is read.
+ * duration (kernel class 6) is the rate at which the chip streams that memory to a kernel without
+ * arithmetic: the practical ceiling beside which the bandwidth of the statistics kernels is read.
  * src: device, 16-byte aligned, bytes a multiple of 16 (else ADASD_ERR_MISALIGNED); sink: device,
  * caller-owned, sink_words >= ceil(bytes / 32768) (else ADASD_ERR_WORKSPACE); bytes == 0
  * does nothing.  Enqueues one kernel on `stream`; allocates nothing and does not synchronise.

@@ -20,14 +20,21 @@ ST_BAD_TOKEN, ST_NONFINITE, ST_ZERO_MASS, ST_OVERFLOW = 1, 2, 4, 8
 
 
 def build_oracle(force: bool = False) -> str:
-    """Compile the oracle with plain gcc -O2 (no fast-math, no intrinsics)."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(
+    """Compile the oracle with plain gcc -O2 (no fast-math, no intrinsics).
+
+    With ADASD_ORACLE_SANITIZE set to a -fsanitize= list ("undefined" or "address,undefined") a second,
+    instrumented library is built at -O1 instead and returned: the sanitizer leg of the CPU tests loads
+    the oracle through it (AddressSanitizer needs its runtime preloaded into the interpreter)."""
+    san = os.environ.get("ADASD_ORACLE_SANITIZE", "")
+    lib = _LIB if not san else os.path.join(_HERE, "libadasd_oracle_san_" + san.replace(",", "_") + ".so")
+    stale = (not os.path.exists(lib)) or os.path.getmtime(lib) < max(
         os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_HERE, "adasd_oracle.h")))
     if force or stale:
-        cmd = ["gcc", "-O2", "-std=c99", "-Wall", "-Wextra", "-fPIC", "-shared", "-fopenmp",
-               "-o", _LIB, _SRC, "-lm"]
+        opt = ["-O2"] if not san else ["-O1", "-g", "-fsanitize=" + san, "-fno-sanitize-recover=all"]
+        cmd = ["gcc"] + opt + ["-std=c99", "-Wall", "-Wextra", "-fPIC", "-shared", "-fopenmp",
+                               "-o", lib, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
-    return _LIB
+    return lib
 
 
 class _VerifyArgs(C.Structure):

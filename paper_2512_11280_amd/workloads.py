@@ -76,15 +76,16 @@ def _sample_tokens(draft_rows: torch.Tensor, gen: torch.Generator) -> torch.Tens
 
 
 def mix_logits(B: int, k: int, V: int, dtype: torch.dtype, gen: torch.Generator,
-               std, spike, alpha: torch.Tensor):
+               std, spike, alpha: torch.Tensor, draw_tokens: bool = True):
     """Target rows N(0, std^2) with `spike` added at one random index per row; draft rows
     alpha*target + (1-alpha)*N(0, std^2).  `std`/`spike` are scalars or [k+1] tensors,
-    `alpha` is [B, k].  Generated one sequence at a time to bound host memory."""
+    `alpha` is [B, k].  Generated one sequence at a time to bound host memory.  draw_tokens=False leaves
+    the token array at 0 (for callers whose tokens come from the drafting call)."""
     std = torch.as_tensor(std, dtype=torch.float32).expand(k + 1).reshape(k + 1, 1)
     spike = torch.as_tensor(spike, dtype=torch.float32).expand(k + 1)
     target = torch.empty(B, k + 1, V, dtype=dtype)
     draft = torch.empty(B, k, V, dtype=dtype)
-    tokens = torch.empty(B, k, dtype=torch.int32)
+    tokens = torch.zeros(B, k, dtype=torch.int32)
     for b in range(B):
         t = torch.randn(k + 1, V, generator=gen, dtype=torch.float32) * std
         idx = torch.randint(0, V, (k + 1,), generator=gen)
@@ -94,7 +95,7 @@ def mix_logits(B: int, k: int, V: int, dtype: torch.dtype, gen: torch.Generator,
         d = a * t[:k] + (1.0 - a) * noise
         target[b] = t.to(dtype)
         draft[b] = d.to(dtype)
-        if k:
+        if k and draw_tokens:
             tokens[b] = _sample_tokens(draft[b].float(), gen)
     return target, draft, tokens
 
@@ -161,8 +162,9 @@ class ClosedLoopSource:
     with the tiny configuration's recipe (std 3, spike 8)."""
 
     def __init__(self, B: int, V: int, k_max: int, dtype=torch.bfloat16,
-                 seed: int = DEFAULT_SEED + 4):
+                 seed: int = DEFAULT_SEED + 4, draw_tokens: bool = True):
         self.B, self.V, self.k_max, self.dtype = B, V, k_max, dtype
+        self.draw_tokens = draw_tokens
         self.gen = torch.Generator().manual_seed(seed)
         self.alpha = 0.5 + 0.4 * torch.rand(B, generator=self.gen)
         self.seed = seed
@@ -171,4 +173,26 @@ class ClosedLoopSource:
         step = torch.where(torch.rand(self.B, generator=self.gen) < 0.5, -0.02, 0.02)
         self.alpha = (self.alpha + step).clamp(0.4, 0.99)
         alpha = self.alpha.reshape(self.B, 1).expand(self.B, self.k_max)
-        return mix_logits(self.B, self.k_max, self.V, self.dtype, self.gen, 3.0, 8.0, alpha)
+        return mix_logits(self.B, self.k_max, self.V, self.dtype, self.gen, 3.0, 8.0, alpha, self.draw_tokens)
+
+
+class ClosedLoopDeviceSource:
+    """The same recipe generated on the GPU (its own random stream): per round target rows [B, k_max+1, V]
+    and draft rows [B, k_max, V] in bf16, resident in device memory.  For the sequences of a closed-loop run
+    that no host-side check replays."""
+
+    def __init__(self, B: int, V: int, k_max: int, seed: int = DEFAULT_SEED + 4, device: str = "cuda"):
+        self.B, self.V, self.k_max, self.device = B, V, k_max, device
+        self.gen = torch.Generator(device=device).manual_seed(seed)
+        self.alpha = 0.5 + 0.4 * torch.rand(B, generator=self.gen, device=device)
+
+    def next_round(self):
+        B, k, V, g, dev = self.B, self.k_max, self.V, self.gen, self.device
+        walk = torch.where(torch.rand(B, generator=g, device=dev) < 0.5, -0.02, 0.02)
+        self.alpha = (self.alpha + walk).clamp(0.4, 0.99)
+        t = torch.randn(B, k + 1, V, generator=g, device=dev) * 3.0
+        idx = torch.randint(0, V, (B, k + 1, 1), generator=g, device=dev)
+        t.scatter_add_(2, idx, torch.full_like(idx, 8.0, dtype=torch.float32))
+        a3 = self.alpha.reshape(B, 1, 1)
+        d = (a3 * t[:, :k] + (1 - a3) * 3.0 * torch.randn(B, k, V, generator=g, device=dev)).to(torch.bfloat16)
+        return t.to(torch.bfloat16), d

@@ -1241,6 +1241,62 @@ def test_closed_loop_rounds_against_oracle(am, wl, oracle, mode):
         assert lens.max() > 1                # the threshold has adapted upwards since
 
 
+@pytest.mark.parametrize("n_hist,cap", [(64, 300), (4060, 4400)], ids=["short_lists", "lists_crossing_the_running_sum_mark"])
+def test_snapshot_then_resume_twice_gives_identical_state(am, wl, n_hist, cap):
+    """Checkpoint and resume of a decoding run: the state copied to the host after five rounds and loaded
+    into a fresh device state twice must give, both times, bit for bit the same outputs and the same final
+    state, and the same decisions, tokens and lists as the run that was never interrupted (whose running
+    sums of long lists were carried from round to round rather than added up again at the load)."""
+    B, K, V, n_rounds, cut = 6, 6, 8192, 10, 5
+    g = torch.Generator().manual_seed(21)
+    host0 = wl.threshold_state(B, cap, g, n_hist=n_hist)
+    src = wl.ClosedLoopSource(B, V, K, dtype=torch.bfloat16, seed=33)
+    rounds = [tuple(x.cuda() for x in src.next_round()) for _ in range(n_rounds)]
+    ws = am.Workspace(B, K, V, torch.bfloat16)
+    names = ("n_accept", "next_token", "H_p", "H_q", "d_js", "p_accept", "accept_mask", "status")
+
+    def bits(v):
+        return v.view(torch.int32) if v.dtype == torch.float32 else v
+
+    def run(state, first, last):
+        outs = []
+        for r in range(first, last):
+            t, d, x = rounds[r]
+            o = am.verify(t, d, x, ws, state=state, seed=5, round0=r, options=am.Options(apply_update=1))
+            torch.cuda.synchronize()
+            outs.append({k: getattr(o, k).clone() for k in names})
+        return outs
+
+    whole = am.State(B, cap).load(host0)
+    run(whole, 0, cut)
+    snapshot = {k: np.array(v, copy=True) for k, v in whole.to_host().items()}
+    rest = run(whole, cut, n_rounds)
+    final = whole.to_host()
+    resumed = []
+    for _ in range(2):
+        st = am.State(B, cap).load(snapshot)
+        outs = run(st, cut, n_rounds)
+        resumed.append((outs, st.to_host(), st.mom.cpu().numpy()))
+    (o1, f1, m1), (o2, f2, m2) = resumed
+    for a, b in zip(o1, o2):
+        for k in names:
+            assert torch.equal(bits(a[k]), bits(b[k])), k
+    for k in f1:
+        assert np.array_equal(f1[k], f2[k]), k
+    assert np.array_equal(m1, m2)
+    # against the uninterrupted run: integers, tokens and the state's lists bit for bit; the posterior to the
+    # rounding of the two ways of forming the lists' sums
+    for a, b in zip(rest, o1):
+        for k in ("n_accept", "next_token", "accept_mask", "status", "H_p", "H_q", "d_js"):
+            assert torch.equal(a[k], b[k]), k
+        assert torch.allclose(a["p_accept"], b["p_accept"], rtol=0, atol=1e-6)
+    for k in final:
+        assert np.array_equal(final[k], f1[k]), k
+    assert (f1["nA"] + f1["nR"] > snapshot["nA"] + snapshot["nR"]).all()      # the lists did grow after the cut
+    if n_hist >= 4000:
+        assert (f1["nA"] >= 4096).any() and (snapshot["nA"] < 4096).all()
+
+
 def test_verify_and_draft_step_replay_from_a_hip_graph(am, wl):
     """The library only enqueues kernels on the caller's stream (no allocation, no synchronisation, no
     memset), so a round can be captured once and replayed.  Every replay, with eager work and
