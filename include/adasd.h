@@ -330,8 +330,10 @@ int adasd_verify_shard_decide(const adasd_verify_args *meta /* host */, const ad
  *        the refined normaliser sums of the local columns;
  *   7. gather into cand_all [G][B];
  *      adasd_verify_shard_settle (replicated) -> next_token of the open sequences from float64 keys, with
- *        ADASD_ST_EXACT_PATH, and tau = +inf for them; where the error bounds of the normalisers still
- *        overlap, ADASD_ST_UNSETTLED is set, the provisional token stays and tau stays finite;
+ *        ADASD_ST_EXACT_PATH, and tau = +inf for them (candidates with identical logits and identical
+ *        noise have identical keys whatever the normalisers are: an exact tie, won by the lower index);
+ *        where the error bounds of the normalisers still overlap, ADASD_ST_UNSETTLED is set, the
+ *        provisional token stays and tau stays finite;
  *   8. steps 6 and 7 once more with exact_sums = 1 (every term of the normaliser sums in float64, about
  *        a millisecond per open sequence and holder at V = 128256) close those: the settle call clears
  *        ADASD_ST_UNSETTLED when it succeeds.  What stays flagged has no sharded form: no element with

@@ -21,7 +21,12 @@ __device__ __forceinline__ void scan_slice(const char* prow, const char* qrow, i
                                            float cp, float cq, int excluded, int col0, uint32_t c1, uint32_t c2,
                                            uint32_t c3, uint32_t k0, uint32_t k1, Top2& best, bool& poison) {
   // col0: vocabulary index of the row's first element (0 unless the row is a column slice); indices,
-  // the excluded token and the noise counters are in vocabulary indices
+  // the excluded token and the noise counters are in vocabulary indices.
+  // kExclude gives a key to every finite logit but the excluded one, also to those whose probability is 0
+  // in float64 (which the float64 path skips).  Such an element cannot win: this mode only runs after the
+  // match test rejected the excluded token x, i.e. ln u1 >= ln p(x) with u1 < 1 - 2^-25, so the rest of the
+  // row holds a mass of at least 3e-8 and some element at least 3e-8 / V of it; its key is above -50 nats
+  // whatever its noise, the key of an element with p < 5e-324 below -720.
   constexpr bool RESIDUAL = MODE == kResidual;
   constexpr int EPV = Elem<DT>::per_vec;
   const int tid = threadIdx.x;
@@ -222,7 +227,7 @@ constexpr int kShardCand = 8;          // candidates a holder exports per sequen
 struct ShardCand {                     // 128 bytes
   double sum_p, sum_q;                 // sum of 2^(z log2 e - c) over the holder's columns, c = the plan's normalisers
   int32_t n, flags;                    // flags: 1 more candidates than the record holds, 2 the sums are float64-exact
-  struct { int32_t idx; float zp, zq; } c[kShardCand];
+  struct Cand { int32_t idx; float zp, zq; } c[kShardCand];
   int32_t pad[2];
 };
 static_assert(sizeof(ShardCand) == 128, "exchange record of the sharded refinement");
@@ -422,39 +427,45 @@ __global__ void __launch_bounds__(kBlock) k_shard_settle(SampleArgs a, int G, fl
   const double bound = exact ? 0x1p-40 : 0x1p-21;
   const double lse_p = residual ? (plan.lse2_p + log(sp) * 1.44269504088896340736) * 0.69314718055994530942 : 0.0;
   const double lse_q = residual ? (plan.lse2_q + log(sq) * 1.44269504088896340736) * 0.69314718055994530942 : 0.0;
-  // candidate number `lane`, `lane + 64`, ... in holder order
-  double best_key = -INFINITY, best_err = 0.0, second_hi = -INFINITY;   // second_hi: largest key + err among the others of this lane
+  // candidate number `lane`, `lane + 64`, ... in holder order; float64 key of one of them
+  auto key_of = [&](const ShardCand::Cand& e, double* err, uint32_t* word) {
+    const int v = e.idx;
+    const U4 w4 = philox4x32_10((uint32_t)v >> 2, c1, c2, c3, a.seed_lo, a.seed_hi);
+    *word = pick_word(w4, v);
+    const double u = ((double)*word + 0.5) * (1.0 / 4294967296.0);
+    const double gn = log(-log(u));
+    *err = 0.0;
+    if (!residual) return (double)e.zp - gn;
+    const double p = exp((double)e.zp - lse_p), q = exp((double)e.zq - lse_q);
+    const double w = p - q;
+    *err = w > 0.0 ? bound * (p + q) / w : INFINITY;
+    return w > 0.0 ? log(w) - gn : -INFINITY;
+  };
+  // pass 1: the best key (lowest index among equal ones), with the inputs it was formed from
+  double best_key = -INFINITY, best_err = 0.0;
   int best_idx = 0x7fffffff, uncertain = 0;
+  float best_zp = 0.f, best_zq = 0.f;
+  uint32_t best_word = 0u;
   int seen = 0;
   for (int g = 0; g < G; ++g) {
     const ShardCand* r = all + (size_t)g * B + b;
     for (int c = 0; c < r->n; ++c, ++seen) {
       if ((seen & 63) != lane) continue;
+      double err;
+      uint32_t word;
+      const double key = key_of(r->c[c], &err, &word);
+      if (residual && !(err < 0.25)) uncertain = 1;
       const int v = r->c[c].idx;
-      const U4 w4 = philox4x32_10((uint32_t)v >> 2, c1, c2, c3, a.seed_lo, a.seed_hi);
-      const double u = ((double)pick_word(w4, v) + 0.5) * (1.0 / 4294967296.0);
-      const double gn = log(-log(u));
-      double key, err = 0.0;
-      if (residual) {
-        const double p = exp((double)r->c[c].zp - lse_p), q = exp((double)r->c[c].zq - lse_q);
-        const double w = p - q;
-        err = w > 0.0 ? bound * (p + q) / w : INFINITY;
-        key = w > 0.0 ? log(w) - gn : -INFINITY;
-        if (!(err < 0.25)) uncertain = 1;
-      } else {
-        key = (double)r->c[c].zp - gn;
-      }
       if (key > best_key || (key == best_key && v < best_idx)) {
-        second_hi = fmax(second_hi, best_key + best_err);
         best_key = key;
         best_err = err;
         best_idx = v;
-      } else {
-        second_hi = fmax(second_hi, key + err);
+        best_zp = r->c[c].zp;
+        best_zq = r->c[c].zq;
+        best_word = word;
       }
     }
   }
-  // across the lanes: the best, and the largest upper end among all the others
   double wk = best_key;
   int wi = best_idx;
 #pragma unroll
@@ -463,14 +474,29 @@ __global__ void __launch_bounds__(kBlock) k_shard_settle(SampleArgs a, int G, fl
     const int oi = __shfl_xor(wi, off);
     if (ok > wk || (ok == wk && oi < wi)) { wk = ok; wi = oi; }
   }
-  const bool mine = best_idx == wi && best_key == wk;
-  double others = mine ? second_hi : fmax(second_hi, best_key + best_err);
-  double werr = mine ? best_err : 0.0;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    others = fmax(others, __shfl_xor(others, off));
-    werr = fmax(werr, __shfl_xor(werr, off));
+  const unsigned long long owner_mask = __ballot(best_idx == wi && best_key == wk);
+  const int owner = owner_mask ? __ffsll((long long)owner_mask) - 1 : 0;
+  const double werr = __shfl(best_err, owner);
+  const float wzp = __shfl(best_zp, owner), wzq = __shfl(best_zq, owner);
+  const uint32_t wword = (uint32_t)__shfl((int)best_word, owner);
+  // pass 2: the largest upper end among the others.  A candidate formed from the very same logits and the
+  // very same noise word as the winner has the winner's key whatever the normalisers are: an exact tie,
+  // which the lower index wins, not a close call.
+  double others = -INFINITY;
+  seen = 0;
+  for (int g = 0; g < G; ++g) {
+    const ShardCand* r = all + (size_t)g * B + b;
+    for (int c = 0; c < r->n; ++c, ++seen) {
+      if ((seen & 63) != lane || r->c[c].idx == wi) continue;
+      double err;
+      uint32_t word;
+      const double key = key_of(r->c[c], &err, &word);
+      if (word == wword && r->c[c].zp == wzp && r->c[c].zq == wzq) continue;
+      others = fmax(others, key + err);
+    }
   }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) others = fmax(others, __shfl_xor(others, off));
   uncertain = __any(uncertain);
   if (lane != 0) return;
   if (total == 0 || overflow || uncertain || wi == 0x7fffffff || (residual && !(wk - werr > others))) {

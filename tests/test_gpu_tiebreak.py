@@ -68,3 +68,27 @@ def test_the_noise_words_of_the_pairs_are_equal_on_the_device_too(am, oracle):
                         draft_len=torch.zeros(1, dtype=torch.int32).cuda(), seed=SEED, options=am.Options(relaxed_off=1))
         torch.cuda.synchronize()
         assert out.next_token.item() == ref["next_token"][0]
+
+
+@pytest.mark.parametrize("kind", ["residual", "bonus", "excluded"])
+def test_column_sharded_round_keeps_the_lowest_index_on_an_exact_tie(am, oracle, kind):
+    """The same tied rows through the column-sharded calls: the two elements of a pair sit in different
+    holders' columns (or both in one), their records travel through the pick and settle calls with equal
+    keys, and every replica must name the lower index."""
+    from paper_2512_11280_amd import workloads as wl
+    from test_gpu_parity import _sharded_decisions, _sharded_tokens
+    for i, j in KNOWN[1]:
+        t, d, x, k = tied_rows(i, j, kind)
+        opt = dict(relaxed_off=1, base_test=1 if kind == "excluded" else 0)
+        ref = oracle.verify(t, d, x, draft_len=np.int32([k]), seed=SEED, **opt)
+        assert ref["next_token"][0] == i and ref["top2_gap"][0] == 0.0
+        batch = wl.VerifyBatch(torch.tensor(t), torch.tensor(d), torch.tensor(x), torch.tensor([k], dtype=torch.int32),
+                               wl.empty_state(1, 8), SEED)
+        options = am.Options(**opt)
+        ctx = _sharded_decisions(am, batch, 4, options=options)
+        outs = ctx[0]
+        _sharded_tokens(am, batch, ctx, outs)
+        for o in outs:
+            st = int(o.status.item())
+            assert o.next_token.item() == i, (kind, i, j, o.next_token.item())
+            assert st & am.binding.ST_EXACT_PATH and not st & am.binding.ST_UNSETTLED, (kind, i, j, st)
