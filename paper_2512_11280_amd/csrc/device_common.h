@@ -146,34 +146,41 @@ __device__ __forceinline__ double wave_max(double v) {
   return v;
 }
 
-// Wavefront reductions on the data-parallel-primitive path: rotations inside each row of 16 lanes
-// leave every lane with its row's result, the four row results are then combined through scalar
-// registers.  Far shorter dependent chains than six LDS permutes.
+// Wavefront reductions on the data-parallel-primitive path: four rotations inside each row of 16 lanes
+// leave every lane with its row's result; row 0's is then added into row 1 and row 2's into row 3
+// (row_bcast:15), rows 0+1 into rows 2 and 3 (row_bcast:31), and lane 63 holds the result, grouped as
+// (r0 + r1) + (r2 + r3).  Seven instructions, against fifteen with the four row results combined through
+// scalar registers, and far shorter dependent chains than six LDS permutes.  All 64 lanes must be active.
 template <int CTRL> __device__ __forceinline__ float dpp_rot(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
 }
 __device__ __forceinline__ float lane_value(float v, int lane) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
+// (Written as one data-parallel instruction per step where the compiler would not make one: from the builtin
+// it makes a move, a canonicalising maximum and the maximum itself, and it has no form for a partial row
+// mask.  A data-parallel operand must not be read in the two instruction slots after the instruction that
+// wrote it, hence the s_nop.)
+#define ADASD_DPP_OP(OP, v, CTRL) asm("s_nop 1\n\t" OP " %0, %0, %0 " CTRL : "+v"(v))
 __device__ __forceinline__ float wave_sum_f(float v) {
   v += dpp_rot<0x121>(v);    // row_ror:1
   v += dpp_rot<0x122>(v);    // row_ror:2
   v += dpp_rot<0x124>(v);    // row_ror:4
   v += dpp_rot<0x128>(v);    // row_ror:8
-  return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
+  ADASD_DPP_OP("v_add_f32_dpp", v, "row_bcast:15 row_mask:0xa bank_mask:0xf");
+  ADASD_DPP_OP("v_add_f32_dpp", v, "row_bcast:31 row_mask:0xc bank_mask:0xf");
+  return lane_value(v, 63);
 }
-// (The maximum is written as one data-parallel instruction per step: from the builtin the compiler makes a
-// move, a canonicalising maximum and the maximum itself.  A data-parallel operand must not be read in the two
-// instruction slots after the instruction that wrote it, hence the s_nop.)
-#define ADASD_DPP_MAX(v, ROT) asm("s_nop 1\n\tv_max_f32_dpp %0, %0, %0 " ROT " row_mask:0xf bank_mask:0xf" : "+v"(v))
 __device__ __forceinline__ float wave_max_f(float v) {
-  ADASD_DPP_MAX(v, "row_ror:1");
-  ADASD_DPP_MAX(v, "row_ror:2");
-  ADASD_DPP_MAX(v, "row_ror:4");
-  ADASD_DPP_MAX(v, "row_ror:8");
-  return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
+  ADASD_DPP_OP("v_max_f32_dpp", v, "row_ror:1 row_mask:0xf bank_mask:0xf");
+  ADASD_DPP_OP("v_max_f32_dpp", v, "row_ror:2 row_mask:0xf bank_mask:0xf");
+  ADASD_DPP_OP("v_max_f32_dpp", v, "row_ror:4 row_mask:0xf bank_mask:0xf");
+  ADASD_DPP_OP("v_max_f32_dpp", v, "row_ror:8 row_mask:0xf bank_mask:0xf");
+  ADASD_DPP_OP("v_max_f32_dpp", v, "row_bcast:15 row_mask:0xa bank_mask:0xf");
+  ADASD_DPP_OP("v_max_f32_dpp", v, "row_bcast:31 row_mask:0xc bank_mask:0xf");
+  return lane_value(v, 63);
 }
-#undef ADASD_DPP_MAX
+#undef ADASD_DPP_OP
 
 __device__ __forceinline__ uint32_t pk_max_f16(uint32_t a, uint32_t b) {
   uint32_t r;
