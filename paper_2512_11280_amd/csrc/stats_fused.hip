@@ -167,7 +167,8 @@ __device__ __forceinline__ float phase2(const uint4 (&xp)[NB], const uint4 (&xq)
 #pragma unroll
     for (int e = 0; e < EPV; e += 2) {
       jsd_push<FAR>(zp[e], zq[e], n, acc0);
-      jsd_push<FAR>(zp[e + 1], zq[e + 1], n, acc1);
+      if (FAR) __builtin_amdgcn_sched_barrier(0);
+      jsd_push<FAR>(zp[e + 1], zq[e + 1], n, FAR ? acc0 : acc1);   // (the long form gets by with one register less)
       if (FAR) __builtin_amdgcn_sched_barrier(0);   // (the long form, rarely taken, must not set the kernel's register count)
     }
     __builtin_amdgcn_sched_barrier(0);     // one vector pair at a time: keeps the number of unpacked values in flight small
@@ -194,7 +195,7 @@ __device__ __forceinline__ void fold_position(const Lse& tp, const Lse& tq, JsNo
 }
 
 template <int DT, int T, int NB>
-__global__ void __launch_bounds__(T, NB <= 2 ? 8 : (NB <= 4 ? 7 : 5))
+__global__ void __launch_bounds__(T, NB <= 4 ? 8 : 5)
 k_stats_fused(RowMap map, FusedGeom g, Workspace ws, VerifyOut vout) {
   warm_kernargs<sizeof(RowMap) + sizeof(FusedGeom) + sizeof(Workspace) + sizeof(VerifyOut)>();
   constexpr int W = T / 64;
