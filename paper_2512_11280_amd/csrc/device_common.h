@@ -226,6 +226,24 @@ template <int DT, int NV> __device__ __forceinline__ float vecs_max(const uint4 
 }
 
 // Phase-1 accumulation of one vector into per-lane sums relative to the reference m.
+// (neg_m = -m: a caller whose reference is wave-uniform hands it over in a vector register; as a scalar it
+// would be the second scalar operand of the multiply-add next to log2(e), which the instruction cannot
+// take, and the compiler copies it into a vector register again and again.)
+template <int DT>
+__device__ __forceinline__ void lse_accum_neg(const uint4& v, float neg_m, float& s0, float& s1, float& u0, float& u1) {
+  constexpr int EPV = Elem<DT>::per_vec;
+  float z[EPV];
+  unpack<DT>(v, z);
+#pragma unroll
+  for (int e = 0; e < EPV; e += 2) {
+    float t0 = fmaf(z[e], kLog2e, neg_m), t1 = fmaf(z[e + 1], kLog2e, neg_m);
+    float e0 = ex2(t0), e1 = ex2(t1);
+    s0 += e0;
+    s1 += e1;
+    u0 = fmaf(fmaxf(t0, -200.f), e0, u0);   // masked logits: (-200) * 0 = 0; a NaN stays one through e
+    u1 = fmaf(fmaxf(t1, -200.f), e1, u1);
+  }
+}
 template <int DT>
 __device__ __forceinline__ void lse_accum(const uint4& v, float m, float& s0, float& s1, float& u0, float& u1) {
   constexpr int EPV = Elem<DT>::per_vec;

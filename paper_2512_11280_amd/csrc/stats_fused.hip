@@ -114,10 +114,12 @@ __device__ __forceinline__ SliceRecord phase1(const uint4 (&xp)[NB], const uint4
   r.mp = flagged(wave_max_f(vecs_max<DT, NB>(xp)));
   r.mq = flagged(wave_max_f(vecs_max<DT, NB>(xq)));
   float ps0 = 0.f, ps1 = 0.f, pu0 = 0.f, pu1 = 0.f, qs0 = 0.f, qs1 = 0.f, qu0 = 0.f, qu1 = 0.f;
+  float neg_mp = -r.mp, neg_mq = -r.mq;
+  asm volatile("" : "+v"(neg_mp), "+v"(neg_mq));   // in vector registers, once
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
-    lse_accum<DT>(xp[j], r.mp, ps0, ps1, pu0, pu1);
-    lse_accum<DT>(xq[j], r.mq, qs0, qs1, qu0, qu1);
+    lse_accum_neg<DT>(xp[j], neg_mp, ps0, ps1, pu0, pu1);
+    lse_accum_neg<DT>(xq[j], neg_mq, qs0, qs1, qu0, qu1);
     __builtin_amdgcn_sched_barrier(0);     // one vector pair at a time: keeps the number of unpacked values in flight small
   }
   r.sp = wave_sum_f(ps0 + ps1);
@@ -195,7 +197,7 @@ __device__ __forceinline__ void fold_position(const Lse& tp, const Lse& tq, JsNo
 }
 
 template <int DT, int T, int NB>
-__global__ void __launch_bounds__(T, NB <= 4 ? 8 : 5)
+__global__ void __launch_bounds__(T, NB <= 4 ? 8 : 4)
 k_stats_fused(RowMap map, FusedGeom g, Workspace ws, VerifyOut vout) {
   warm_kernargs<sizeof(RowMap) + sizeof(FusedGeom) + sizeof(Workspace) + sizeof(VerifyOut)>();
   constexpr int W = T / 64;
