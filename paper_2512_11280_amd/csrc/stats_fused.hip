@@ -10,14 +10,15 @@
 // runs phase 2 (the JS sum) on the registers it still holds.
 //
 // One workgroup per item, T threads, NB vectors per thread and row held in registers from the load to
-// the end of phase 2.  The kernel is bound by the vector ALU (about 36 instructions per logit pair, five
-// of them transcendental, against two bytes of bf16 each), so what matters is the instruction count
-// per pair -- many pairs per thread, because the reductions and the exchange cost a fixed number of
-// instructions per item -- and enough wavefronts per SIMD to keep it issuing while other workgroups
-// load or wait.  (Also built and measured: persistent workgroups with two and with three register
-// buffers, the loads and the exchange of the next items in flight behind the arithmetic of the current
-// one.  They need about a hundred registers, i.e. four wavefronts per SIMD, and the folds that one
-// wavefront does for its workgroup between two barriers then stand in the open: 67-77 us against 48.)
+// the end of phase 2.  The kernel is bound by the vector ALU (about 43 issued instructions per logit pair,
+// 36 of them the arithmetic itself and five of those transcendental, against two bytes of bf16 each), so
+// what matters is the instruction count per pair -- many pairs per thread, because the reductions and the
+// exchange cost a fixed number of instructions per item -- and enough wavefronts per SIMD to keep it
+// issuing while other workgroups load or wait: with four vectors per thread and row the kernel fits 64
+// registers, i.e. eight wavefronts per SIMD.  (Also built and measured: persistent workgroups with two and
+// with three register buffers, the loads and the exchange of the next items in flight behind the arithmetic
+// of the current one.  They need about a hundred registers, i.e. four wavefronts per SIMD, and the folds
+// that one wavefront does for its workgroup between two barriers then stand in the open: 56-80 us against 47.)
 //
 // Hand-off between the workgroups of a position: self-validating 64-bit words (two floats, valid flag
 // in the low mantissa bit of the low float; a cleared word is 0) written and read with agent-scope

@@ -33,12 +33,12 @@ def _slice_ref(ref, i, B):
 
 
 def _progress(line):
-    """pytest holds the test's output back; a line in the scratch folder of the GPU runs shows that a long
-    run is alive."""
+    """pytest holds a test's output back; with ADASD_PROGRESS_LOG set to a file name the lines also go there,
+    so that a long run (ADASD_CLOSED_LOOP_ROUNDS=1000 takes minutes) can be seen to be alive."""
     print(line, flush=True)
-    folder = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(folder):
-        with open(os.path.join(folder, "closed_loop_progress.log"), "a") as f:
+    path = os.environ.get("ADASD_PROGRESS_LOG")
+    if path:
+        with open(path, "a") as f:
             f.write(line + "\n")
 
 
