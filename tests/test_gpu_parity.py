@@ -414,7 +414,7 @@ def test_literal_variant_status_and_float64_path(am, wl, oracle):
 
 # ------------------------------------------------------------------------------- long histories
 @pytest.mark.parametrize("n_hist,cap,path", [(64, 512, 1), (700, 1024, 1), (700, 1024, 2), (5000, 5003, 1), (40000, 40100, 1),
-                                             (64, 20000, 1), (5000, 20000, 1), (17000, 20000, 1)])
+                                             (64, 20000, 1), (5000, 20000, 1), (17000, 20000, 1), (131072, 131100, 2)])
 @pytest.mark.parametrize("opt", [dict(), dict(list_update=1, base_test=1), dict(bw_rule=1, reject_rule=1)],
                          ids=["default", "literal", "scott-map"])
 def test_long_history_lists_take_the_workgroup_per_position_path(am, wl, oracle, n_hist, cap, opt, path):
