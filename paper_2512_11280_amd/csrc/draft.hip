@@ -35,7 +35,7 @@ __device__ __forceinline__ RowResult fold_row_shared(const Workspace& ws, int rh
   if (ok) {
     const double l2s = log2_acc(sw);
     res.lse2 = (double)M + l2s;
-    res.H = (float)(kLn2 * (l2s - (double)uw / (double)sw));
+    res.H = fmaxf((float)(kLn2 * (l2s - (double)uw / (double)sw)), 0.f);   // (a one-hot row: a few 1e-8 either side of 0)
     res.bad = 0;
   } else {
     res.lse2 = NAN;

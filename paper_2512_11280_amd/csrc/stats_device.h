@@ -77,7 +77,7 @@ __device__ __forceinline__ RowResult fold_lanes(const Lse& t) {
   if (ok) {
     const double l2s = log2_acc(sw);
     res.lse2 = (double)M + l2s;
-    res.H = (float)(kLn2 * (l2s - (double)uw / (double)sw));
+    res.H = fmaxf((float)(kLn2 * (l2s - (double)uw / (double)sw)), 0.f);   // (a one-hot row: a few 1e-8 either side of 0)
     res.bad = 0;
   } else {
     res.lse2 = NAN;
@@ -106,7 +106,12 @@ __device__ __forceinline__ RowResult fold_row(const Workspace& ws, int rho, int 
 // relative to its own row's offset (op, oq: the row's log-sum-exp in nats rounded to float, 0 for a row
 // whose offset is below 32: next to a large offset z - o is exact for every element of any weight), the
 // difference of the two is kept with its rounding error (two floats), and so is the rest of the
-// normalisers' difference; log2(e) is carried in two floats as well.
+// normalisers' difference.  The factor log2(e) is the SAME float constant everywhere, in the normalisers
+// (which are log2 sum 2^(z k) with k that constant) and in the element's log ratio: what comes out is the
+// log ratio of the two distributions at a temperature k / log2(e) = 1 - 1.3e-8, a relative change of that
+// size.  (Correcting the constant in one place only, e.g. with its low part here, would put 1.3e-8 of a
+// row's offset into every log ratio: 3.7e-6 at an offset of 193 nats, which showed in the distance of two
+// one-hot rows that far apart.)
 struct JsNorm {
   float cp, cq, dc_hi, dc_lo, op, oq;
   int far;
@@ -122,7 +127,7 @@ __device__ __forceinline__ JsNorm js_norm(const RowResult& rp, const RowResult& 
     const double lp = rp.lse2 * kLn2, lq = rq.lse2 * kLn2;
     n.op = fabs(lp) >= 32.0 ? (float)lp : 0.f;
     n.oq = fabs(lq) >= 32.0 ? (float)lq : 0.f;
-    dc -= ((double)n.oq - (double)n.op) * 1.44269504088896340736;
+    dc -= ((double)n.oq - (double)n.op) * (double)kLog2e;   // (the float constant: see below)
   }
   n.dc_hi = (float)dc;
   n.dc_lo = n.far ? (float)(dc - (double)n.dc_hi) : 0.f;
@@ -147,7 +152,6 @@ constexpr float kJsC1 = -0.010407020374654045f;      // -2 * ln2^3 / 64
 constexpr float kJsC2 = 0.0005555649227678517f;      // 2 * ln2^5 / 576
 constexpr float kJsSmall = 0.25f;
 
-constexpr float kLog2eLo = 1.92596299e-08f;          // log2(e) - (double)(float)log2(e)
 
 template <bool FAR>
 __device__ __forceinline__ void jsd_push(float zp, float zq, const JsNorm& n, float& acc) {
@@ -158,7 +162,7 @@ __device__ __forceinline__ void jsd_push(float zp, float zq, const JsNorm& n, fl
     const float a = zq - n.oq, c = n.op - zp;               // delta = (a + c) log2(e) - dc
     const float hi = a + c, t = hi - a;
     const float lo = (a - (hi - t)) + (c - t);              // a + c = hi + lo exactly
-    delta = fmaf(hi, kLog2e, -n.dc_hi) + (fmaf(lo, kLog2e, -n.dc_lo) + hi * kLog2eLo);
+    delta = fmaf(hi, kLog2e, -n.dc_hi) + fmaf(lo, kLog2e, -n.dc_lo);
   } else {
     delta = fmaf(zq - zp, kLog2e, -n.dc_hi);
   }

@@ -287,6 +287,33 @@ def test_rows_with_normalisers_far_apart(am, wl, oracle, dtype, path):
     assert rel.max() < 1e-5
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_nearly_one_hot_rows_with_offsets_far_apart(am, wl, oracle, dtype, path):
+    """Both rows put (nearly) all their mass on the same token while their offsets differ by hundreds of
+    nats: the distance is a few 1e-8 or less, and an inconsistency of 1e-8 of an OFFSET in the log ratios
+    would show as 1e-6.  Found by a randomised sweep (rows scaled by 12 and shifted by +-80): the factor
+    log2(e) has to be the same float constant in the normalisers and in the log ratios."""
+    V, K = 4104, 6
+    g = torch.Generator().manual_seed(41)
+    t = 36.0 * torch.randn(1, K + 1, V, generator=g)
+    d = torch.empty(1, K, V)
+    shifts = [(193.0, 6.6), (-250.0, 120.0), (40.0, -35.0), (209.0, 5.7), (0.0, 300.0), (-60.0, -58.0)]
+    for i, (sp, sq) in enumerate(shifts):
+        top = int(torch.argmax(t[0, i]))
+        t[0, i] += sp - t[0, i, top]                     # the largest logit sits at the offset itself
+        d[0, i] = 0.9 * (t[0, i] - sp) + sq              # same ranking, other scale and offset
+    tok = torch.full((1, K), 17, dtype=torch.int32)
+    batch = wl.VerifyBatch(t.to(dtype), d.to(dtype), tok, None, wl.empty_state(1, 8), 5)
+    out, _, _ = G.run_gpu(am, batch, stats_path=path)
+    ref = G.run_oracle(oracle, batch)
+    print(f"[one-hot rows {dtype}] d gpu:", out.d_js[0].cpu().numpy(), "oracle:", ref["d_js"][0], flush=True)
+    rep = G.compare_verify(out, ref)
+    _report("one-hot rows", rep)
+    err = np.abs(out.d_js[0].cpu().numpy().astype(np.float64) - ref["d_js"][0])
+    assert (err <= 1e-5 * ref["d_js"][0] + 2e-7).all(), err        # well inside the contract's 1e-6
+    assert (out.H_p >= 0).all() and (out.H_q >= 0).all()
+
+
 # ------------------------------------------------------------------------------- options
 @pytest.mark.parametrize("opt", [dict(reject_rule=1), dict(relaxed_off=1), dict(bw_rule=1),
                                  dict(kde_min_n=100)])
