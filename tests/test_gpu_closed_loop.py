@@ -22,6 +22,8 @@ import gpu_util as G
 pytestmark = pytest.mark.gpu
 
 ROUNDS = int(os.environ.get("ADASD_CLOSED_LOOP_ROUNDS", "300"))
+# "literal": the verification loop as Algorithm 1 writes it (match test, appends inside the loop, MAP rule)
+LITERAL = os.environ.get("ADASD_CLOSED_LOOP_MODE", "default") == "literal"
 
 
 def _slice_ref(ref, i, B):
@@ -58,7 +60,7 @@ def test_closed_loop_at_size_against_the_oracle(oracle):
     state = am.State(B, cap)
     host = new_state(n_w, cap)
     out = am.binding.alloc_verify_result(B, W)
-    opts = am.Options(apply_update=1)
+    opts = am.Options(apply_update=1, base_test=1, list_update=1, reject_rule=1) if LITERAL else am.Options(apply_update=1)
     H = torch.empty(B, dtype=torch.float32, device="cuda")
     stop = torch.empty(B, dtype=torch.uint8, device="cuda")
     dst = torch.empty(B, dtype=torch.int32, device="cuda")
@@ -127,7 +129,7 @@ def test_closed_loop_at_size_against_the_oracle(oracle):
         accepted += int(out.n_accept.sum())
 
         batch = wl.VerifyBatch(th, dh, torch.tensor(x_ref), torch.tensor(dl_ref), host, seed, r)
-        ref = G.run_oracle(oracle, batch, seq_id=watched)
+        ref = G.run_oracle(oracle, batch, options=opts, seq_id=watched)
         got = {k: getattr(out, k)[widx] for k in
                ("n_accept", "next_token", "H_p", "H_q", "d_js", "p_accept", "accept_mask", "status")}
         g_lens = lens[widx].cpu().numpy()
@@ -164,7 +166,7 @@ def test_closed_loop_at_size_against_the_oracle(oracle):
               f"including the per-step stop check), sequence-rounds compared {compared_rounds} of {ROUNDS * n_w}, "
               f"parted: {parted}")
     final = state.to_host()
-    if ROUNDS >= 300:                                     # a replayed list has passed the mark from which the
+    if ROUNDS >= 300 and not LITERAL:                     # a replayed list has passed the mark from which the
         assert host["nA"].max() >= 4096                   # state carries running sums, and the capacity split
     assert (final["nA"] + final["nR"] > 0).all()
     assert final["T_G"].min() > 0.0                       # every threshold has left its initial value
