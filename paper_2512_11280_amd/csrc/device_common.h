@@ -312,8 +312,9 @@ __device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c
   for (int r = 0; r < 10; ++r) {
     uint64_t a = (uint64_t)0xD2511F53u * c0;
     uint64_t b = (uint64_t)0xCD9E8D57u * c2;
-    uint32_t n0 = (uint32_t)(b >> 32) ^ c1 ^ k0;
-    uint32_t n2 = (uint32_t)(a >> 32) ^ c3 ^ k1;
+    // (three-input exclusive or in one instruction: left to itself the compiler makes two of each)
+    uint32_t n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(b >> 32), c1, k0, 0x96);
+    uint32_t n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(a >> 32), c3, k1, 0x96);
     c1 = (uint32_t)b;
     c3 = (uint32_t)a;
     c0 = n0;

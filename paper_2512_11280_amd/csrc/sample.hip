@@ -89,7 +89,7 @@ __device__ __forceinline__ void scan_slice(const char* prow, const char* qrow, i
 }
 
 template <int DT>
-__global__ void __launch_bounds__(kBlock, 6) k_sample(SampleArgs a, int S, Workspace ws) {
+__global__ void __launch_bounds__(kBlock, 5) k_sample(SampleArgs a, int S, Workspace ws) {
   warm_kernargs<sizeof(SampleArgs) + sizeof(int) + sizeof(Workspace)>();
   const int b = blockIdx.y, s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const SamplePlan plan = ws.plan[b];
@@ -233,7 +233,7 @@ struct ShardCand {                     // 128 bytes
 static_assert(sizeof(ShardCand) == 128, "exchange record of the sharded refinement");
 
 template <int DT>
-__global__ void __launch_bounds__(kBlock, 6) k_shard_scan(SampleArgs a, int S, int col0, Workspace ws) {
+__global__ void __launch_bounds__(kBlock, 5) k_shard_scan(SampleArgs a, int S, int col0, Workspace ws) {
   const int b = blockIdx.y, s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const SamplePlan plan = ws.plan[b];
   if (!plan.valid) return;
